@@ -1,0 +1,285 @@
+#!/usr/bin/env python3
+"""Benchmark of the clustered-head decode attention path on one MI355X.
+
+A step = one decode token for every batch row through the attention of ALL layers of the configuration
+(scores of each cluster over the compact K cache, stable softmax, shared probabilities applied to every head's
+own V cache).  Caches, queries and cluster maps are resident in HBM before the timed region; membership comes
+from the library's own feature + k-means + compaction kernels (or from the drawn partition for the configurations
+that prescribe one).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config cfg2]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import re
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--context", type=int, default=0, help="override the number of cached tokens (cfg4: 640 or 2048)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--no-phase-timing", action="store_true")
+    return ap.parse_args()
+
+
+class Layer:
+    __slots__ = ("k", "q", "kfull", "kc", "v", "h2c", "rep", "out")
+
+
+def build_layers(cfg, W, C, torch, keep_full_k):
+    """Allocate and fill every layer's tensors on the device; run membership + compaction through the library."""
+    dev = "cuda"
+    B, H, d, T, T_cap = cfg.B, cfg.H, cfg.d, cfg.T, cfg.T_cap
+    tdt = torch.float32 if cfg.dtype == W.F32 else torch.bfloat16
+    layers = []
+    t_member = 0.0
+    for l in range(cfg.L):
+        k = cfg.ks[l]
+        L = Layer()
+        L.k = k
+        seed = cfg.seed * 100003 + l * 17
+        groups = None
+        if cfg.membership == "planted":
+            groups = W.planted_partition(W.rng(cfg.seed, l, "planted"), B, H, k)
+            kfull = W.device_centroid_plus_noise(groups, k, T_cap, d, cfg.dtype, seed + 1, dev)
+            q5 = W.device_centroid_plus_noise(groups, k, W.N_TOK, d, cfg.dtype, seed + 3, dev)
+            L.q = W.device_centroid_plus_noise(groups, k, 1, d, cfg.dtype, seed + 5, dev)[:, :, 0, :].contiguous()
+        else:
+            kfull = W.device_normal((B, H, T_cap, d), cfg.dtype, seed + 1, dev)
+            q5 = W.device_normal((B, H, W.N_TOK, d), cfg.dtype, seed + 3, dev)
+            L.q = W.device_normal((B, H, d), cfg.dtype, seed + 5, dev)
+        L.v = W.device_normal((B, H, T_cap, d), cfg.dtype, seed + 7, dev)
+        L.out = torch.empty((B, H, d), dtype=torch.float32, device=dev)
+
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        if cfg.membership in ("kmeans", "planted"):
+            if cfg.membership == "planted":
+                init = W.one_head_per_group(W.rng(cfg.seed, l, "init"), groups, k)
+            else:
+                init = W.distinct_heads(W.rng(cfg.seed, l, "init"), B, H, k)
+            feat = C.chai_score_features(q5, kfull, W.N_TOK, cfg.scale)
+            L.h2c, L.rep, _, _ = C.chai_assign_clusters(feat, W.host_to_torch(init, dev))
+        else:
+            g = W.rng(cfg.seed, l, "member")
+            h2c, rep = (W.sized_membership(g, B, H, cfg.sizes) if cfg.membership == "skewed"
+                        else W.random_membership(g, B, H, k))
+            L.h2c, L.rep = W.host_to_torch(h2c, dev), W.host_to_torch(rep, dev)
+        L.kc = torch.empty((B, k, T_cap, d), dtype=tdt, device=dev)
+        C.chai_compact_kcache(kfull, L.rep, L.kc, T)
+        torch.cuda.synchronize()
+        t_member += time.perf_counter() - t0
+        L.kfull = kfull if keep_full_k else None
+        del kfull, q5
+        layers.append(L)
+    return layers, t_member
+
+
+def timed_steps(fn, steps, warmup, torch):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        fn()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return e0.elapsed_time(e1) / steps, wall
+
+
+def phase_timing(layers, cfg, ws, C, torch, steps):
+    """Average duration of the score kernel and of the value kernel per launch, from HIP events recorded on the
+    launch stream around each phase call (a separate pass, so the events do not perturb the headline timing)."""
+    n = len(layers) * steps
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
+    i = 0
+    for _ in range(steps):
+        for L in layers:
+            a, b, c = ev[i]
+            i += 1
+            a.record()
+            C.chai_decode_scores(L.q, L.kc, L.rep, cfg.T, cfg.scale, ws)
+            b.record()
+            C.chai_decode_values(L.v, L.h2c, L.rep, cfg.T, L.out, ws)
+            c.record()
+    torch.cuda.synchronize()
+    per_layer = {}
+    i = 0
+    for _ in range(steps):
+        for li, L in enumerate(layers):
+            a, b, c = ev[i]
+            i += 1
+            s, v = per_layer.setdefault(li, [0.0, 0.0])
+            per_layer[li] = [s + a.elapsed_time(b), v + b.elapsed_time(c)]
+    return {li: (s / steps, v / steps) for li, (s, v) in per_layer.items()}
+
+
+def read_traffic(cfg_name):
+    """HBM bytes per value-kernel launch from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"value_kernel_{cfg_name}_hbm_traffic.txt")
+    try:
+        m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
+        return float(m.group(1)) if m else None
+    except OSError:
+        return None
+
+
+def cpu_baseline(cfg, layers, W, torch):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: every batch row of up to 8 evenly
+    spaced layers, timed per layer, scaled to a full step by each layer's cluster count.  The same outputs are
+    compared with the GPU's (parity re-check on the timed tensors)."""
+    import numpy as np
+    from oracle import chai_oracle as O
+    n_s = min(len(layers), 8)
+    idx = sorted(set(int(round(i * (len(layers) - 1) / max(n_s - 1, 1))) for i in range(n_s)))
+    by_k, worst, spent = {}, 0.0, 0.0
+    for li in idx:
+        L = layers[li]
+        k = L.k
+        h2c, rep = L.h2c.cpu().numpy(), L.rep.cpu().numpy()
+        q, v, kc = W.torch_to_host_bits(L.q), W.torch_to_host_bits(L.v), W.torch_to_host_bits(L.kc)
+        # the oracle indexes representatives in a full-size K cache: put the compact rows back in place
+        kfull = np.zeros_like(v)
+        for b in range(cfg.B):
+            for j in range(k):
+                if rep[b, j] >= 0:
+                    kfull[b, rep[b, j]] = kc[b, j]
+        del kc
+        t0 = time.perf_counter()
+        ref = O.clustered_decode(q, kfull, v, h2c, rep, cfg.T, cfg.scale)
+        dt = time.perf_counter() - t0
+        spent += dt
+        by_k.setdefault(k, []).append(dt)
+        got = L.out.cpu().numpy().astype(np.float64)
+        worst = max(worst, float((np.abs(got - ref).max(-1) / np.abs(ref).max(-1)).max()))
+        del kfull, v
+    mean_k = {k: sum(v) / len(v) for k, v in by_k.items()}
+    known = sorted(mean_k)
+    # a cluster count that was not sampled takes the time of the nearest sampled one, scaled by rows streamed
+    def layer_s(k):
+        if k in mean_k:
+            return mean_k[k]
+        kn = min(known, key=lambda x: abs(x - k))
+        return mean_k[kn] * (k + cfg.H) / (kn + cfg.H)
+    step_s = sum(layer_s(L.k) for L in layers)
+    return {"value": cfg.B / step_s, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+            "sample": f"all {cfg.B} batch rows of layers {idx} ({spent:.2f} s of oracle time), scaled to all "
+                      f"{cfg.L} layers by cluster count (extrapolated)",
+            "ms_per_step": step_s * 1e3, "parity_worst_normwise_err": worst}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import dataclasses
+
+    import torch
+
+    import paper_2403_08058_amd as C
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP library has no CPU fallback", file=sys.stderr)
+        sys.exit(3)
+    torch.cuda.set_device(0)
+
+    cfg = W.CONFIGS[args.config]
+    if args.context:
+        cfg = dataclasses.replace(cfg, T=args.context, T_cap=max(cfg.T_cap, args.context))
+    B, H, d, T = cfg.B, cfg.H, cfg.d, cfg.T
+
+    layers, t_member = build_layers(cfg, W, C, torch, keep_full_k=not args.no_dense)
+    kmax = max(cfg.ks)
+    ws = C.alloc_workspace(B, H, H, T, d, cfg.dtype)       # sized for the dense call; serves every layer
+
+    def clustered_step():
+        for L in layers:
+            C.chai_decode_attention(L.q, L.kc, L.v, L.h2c, L.rep, T, cfg.scale, L.out, ws)
+
+    def dense_step():
+        for L in layers:
+            C.chai_dense_decode_attention(L.q, L.kfull, L.v, T, cfg.scale, L.out, ws)
+
+    dense_ms = None
+    if not args.no_dense:
+        dense_ms, _ = timed_steps(dense_step, max(args.steps // 2, 3), args.warmup, torch)
+    ms, wall_ms = timed_steps(clustered_step, args.steps, args.warmup, torch)
+
+    alg_bytes = cfg.clustered_bytes_per_step()
+    result = {
+        "metric": "clustered decode-attn tokens/s + achieved HBM GB/s vs peak, vs dense MHA",
+        "value": B / (ms * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == W.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: {cfg.L} layers x {H} heads x d{d}, batch {B}, context {T}, "
+                               f"clusters/layer {sorted(set(cfg.ks))}, membership {cfg.membership}",
+                   "layers": cfg.L, "heads": H, "head_dim": d, "batch": B, "context": T},
+        "algorithmic_GBps": alg_bytes / (ms * 1e-3) / 1e9,
+        "frac_of_hbm_peak": alg_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "algorithmic_bytes_per_step": alg_bytes,
+        "host_wall_ms_per_step": wall_ms,
+        "membership_and_compaction_s": t_member,
+        "k_cache_bytes_saved": cfg.k_bytes_saved(),
+        "k_cache_fraction_saved": cfg.k_bytes_saved() / (cfg.L * B * H * T * d * cfg.elem_bytes),
+    }
+    if dense_ms is not None:
+        result["dense_mha"] = {"ms_per_step": dense_ms, "tokens_per_s": B / (dense_ms * 1e-3),
+                               "GBps": cfg.dense_bytes_per_step() / (dense_ms * 1e-3) / 1e9,
+                               "speedup_clustered_over_dense": dense_ms / ms,
+                               "ideal_speedup_by_bytes": cfg.dense_bytes_per_step() / alg_bytes}
+
+    if not args.no_phase_timing:
+        ph = phase_timing(layers, cfg, ws, C, torch, max(min(args.steps, 10), 2))
+        e = cfg.elem_bytes
+        # dominant kernel: the value kernel (streams B*H*T*d elements of V per launch, the same for every layer)
+        v_ms = sum(v for _, v in ph.values()) / len(ph)
+        v_bytes = B * H * T * d * e + B * H * d * 4
+        s_bytes = sum(B * L.k * T * d * e for L in layers) / len(layers)
+        s_ms = sum(s for s, _ in ph.values()) / len(ph)
+        ach = v_bytes / (v_ms * 1e-3) / 1e9
+        result["roofline"] = {"bound": "hbm", "kernel": "value_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
+                              "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": read_traffic(cfg.name),
+                              "bytes_per_launch": v_bytes, "avg_launch_ms": v_ms}
+        result["score_kernel"] = {"avg_launch_ms": s_ms, "avg_bytes_per_launch": s_bytes,
+                                  "achieved_GBps": s_bytes / (s_ms * 1e-3) / 1e9}
+
+    if not args.no_cpu_baseline:
+        clustered_step()
+        torch.cuda.synchronize()
+        result["cpu_baseline"] = cpu_baseline(cfg, layers, W, torch)
+
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,222 @@
+/*
+ * chai.h -- C ABI of the MI355X (gfx950) clustered-head decode attention library.
+ *
+ * CHAI (Clustered Head Attention): per layer and per request the attention
+ * heads are grouped into clusters by k-means over the attention scores they
+ * produce on the first few tokens; afterwards only one representative head
+ * per cluster computes softmax(q K^T), the keys of the other heads are
+ * dropped from the cache, and every head applies its cluster's probabilities
+ * to its own values.
+ *
+ * Conventions for every entry point
+ *  - All tensor pointers are DEVICE pointers owned by the caller.  The
+ *    library allocates nothing, frees nothing and keeps no pointer after the
+ *    call returns.  There is no global state.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls only enqueue work on it: no synchronisation, no host read-back.
+ *    Cluster maps produced by one call are consumed by the next on the device.
+ *  - Tensors are dense, row-major, last index fastest, in the shapes written
+ *    next to each argument.  `dtype` (CHAI_F32 or CHAI_BF16) is the storage
+ *    type of q, K and V; bf16 is the upper half of an IEEE fp32 word.  All
+ *    arithmetic accumulates in fp32 (fp64 in chai_assign_clusters and
+ *    chai_score_features); outputs are fp32.
+ *  - q/K/V base pointers must be 16-byte aligned; d must be 128.
+ *  - Arguments are checked on the host before anything is launched; on an
+ *    argument error nothing is enqueued and outputs are untouched.  Contents
+ *    of device maps (cluster ids, representative ids) cannot be checked on
+ *    the host; kernels clamp them into range instead of faulting, and the
+ *    result for an out-of-range map entry is unspecified.
+ *  - One call handles one layer.  B = batch rows (independent requests),
+ *    H = heads, k = cluster slots of this layer, T = cached tokens attended
+ *    to (the current token included), d = head dimension.
+ *  - Return value: CHAI_OK or one of the error codes below.
+ */
+#ifndef CHAI_H
+#define CHAI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    CHAI_OK = 0,
+    CHAI_ERR_NULL = 1,        /* a required pointer is NULL                          */
+    CHAI_ERR_SHAPE = 2,       /* a size is out of range or inconsistent              */
+    CHAI_ERR_DTYPE = 3,       /* dtype is neither CHAI_F32 nor CHAI_BF16             */
+    CHAI_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or smaller than required */
+    CHAI_ERR_UNSUPPORTED = 5, /* valid request this build does not implement (d != 128, ...) */
+    CHAI_ERR_HIP = 6,         /* the HIP runtime reported an error at launch         */
+    CHAI_ERR_ALIGN = 7        /* a tensor pointer is not 16-byte aligned             */
+};
+
+enum { CHAI_F32 = 0, CHAI_BF16 = 1 };
+
+/* Library version, major * 100 + minor. */
+int chai_version(void);
+
+/* Static string for a status code (never NULL). */
+const char *chai_status_string(int status);
+
+/*
+ * Clustering features (Section 3.3: the attention scores of the first tokens
+ * of a request predict cluster membership; Section 3.1: the compared
+ * quantity is f(Q,K) = softmax(Q K^T); Section 2: decoder-only, so causal).
+ *
+ * For every (b,h): the n_tok x n_tok causal attention matrix of the first
+ * n_tok positions, A[i][j] = softmax_j(scale * q_i . k_j) for j <= i and 0
+ * for j > i, flattened row-major into feat[b][h][i*n_tok + j] (fp32).
+ *
+ *   q5    [B,H,*,d]  element (b,h,i,c) at (b*H+h)*q_head_stride + i*d + c
+ *   k5    [B,H,*,d]  element (b,h,j,c) at (b*H+h)*k_head_stride + j*d + c
+ *                    (strides in elements, >= n_tok*d, multiples of 8; lets
+ *                    the keys be read in place from a cache with stride
+ *                    T_cap*d)
+ *   feat  [B,H,n_tok*n_tok] fp32, written
+ * 1 <= n_tok <= 8.  Scores and the softmax are evaluated in fp64 and rounded
+ * once to fp32.
+ */
+int chai_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int d, int dtype,
+                        int64_t q_head_stride, int64_t k_head_stride, float scale, float *feat,
+                        void *stream);
+
+/*
+ * Cluster membership by K-Means (Section 3.5: K-Means on the observed
+ * activations once five tokens are processed, then fixed for the request;
+ * Section 3.2: clustering error = sum of squared distances to the closest
+ * centre).  One independent problem per batch row.  Lloyd iterations in
+ * fp64 with separately rounded multiplies and adds:
+ *   1. centre j starts at feat[b][init_heads[b][j]];
+ *   2. every head goes to the centre at the smallest squared Euclidean
+ *      distance (ties: lowest j);
+ *   3. each centre left without heads, in ascending j, takes the head that is
+ *      farthest from its own centre among heads of clusters holding at least
+ *      two heads (ties: lowest head; if that distance is 0 the centre stays
+ *      empty);
+ *   4. stop if no head changed cluster (never after the first pass);
+ *   5. non-empty centres move to the mean of their heads (summed in head
+ *      order, divided by the count);
+ *   6. at most max_iter passes;
+ *   7. clusters are numbered by their lowest member head, which is the
+ *      cluster's representative.
+ *
+ *   feat            [B,H,F] fp32
+ *   init_heads      [B,k] int32, distinct head ids in [0,H) (the caller's
+ *                   seeded choice; the library draws no random numbers)
+ *   head_to_cluster [B,H] int32, written: canonical cluster id of each head
+ *   rep_heads       [B,k] int32, written: representative of cluster j, -1 for
+ *                   j >= n_clusters[b]
+ *   n_clusters      [B] int32, written: number of non-empty clusters
+ *   iters           [B] int32, written if not NULL: assignment passes run
+ * Limits: 1 <= k <= H <= 256, 1 <= F <= 64, k*F <= 7168, 1 <= max_iter
+ * (beyond them: CHAI_ERR_UNSUPPORTED).  The outputs are bit-identical to the
+ * sequential algorithm above for the same feat bits.
+ */
+int chai_assign_clusters(const float *feat, int B, int H, int F, int k, const int32_t *init_heads,
+                         int max_iter, int32_t *head_to_cluster, int32_t *rep_heads,
+                         int32_t *n_clusters, int32_t *iters, void *stream);
+
+/*
+ * K-cache pruning (Section 3.5: once membership is fixed, the keys of the
+ * pruned heads are removed; Section 4.3 / Fig. 3: all values are kept).
+ *   k_compact[b][j][t][:] = k_full[b][rep_heads[b][j]][t][:]   for t < T.
+ * Cluster slots with rep_heads[b][j] < 0 and rows t >= T are not written.
+ *
+ *   k_full    [B,H,T_cap,d]   read
+ *   rep_heads [B,k] int32     read on the device
+ *   k_compact [B,k,Tc_cap,d]  written; must not overlap k_full
+ * 0 <= T <= min(T_cap, Tc_cap), 1 <= k <= H.
+ */
+int chai_compact_kcache(const void *k_full, const int32_t *rep_heads, void *k_compact, int B, int H,
+                        int k, int T, int T_cap, int Tc_cap, int d, int dtype, void *stream);
+
+/*
+ * Cache growth by one token (Section 2: keys and values of prior tokens are
+ * cached; Section 3.5: keys of pruned heads are not stored).
+ *   k_compact[b][j][pos][:] = k_new[b][rep_heads[b][j]][:]   (rep >= 0)
+ *   v_cache[b][h][pos][:]   = v_new[b][h][:]
+ *
+ *   k_new, v_new [B,H,d]; k_compact [B,k,Tc_cap,d]; v_cache [B,H,T_cap,d]
+ * 0 <= pos < min(T_cap, Tc_cap).
+ */
+int chai_append_kv(const void *k_new, const void *v_new, const int32_t *rep_heads, void *k_compact,
+                   void *v_cache, int B, int H, int k, int pos, int Tc_cap, int T_cap, int d,
+                   int dtype, void *stream);
+
+/*
+ * Bytes of scratch chai_decode_attention / chai_dense_decode_attention need
+ * for these sizes (0 on invalid sizes).  For the dense call pass k = H.  The
+ * value never decreases when B, H, k or T grows, so a workspace sized for the
+ * cache capacity serves every shorter context.
+ */
+size_t chai_decode_workspace_bytes(int B, int H, int k, int T, int d, int dtype);
+
+/*
+ * One decode step of clustered-head attention for one layer (Sections 3.4
+ * and 3.5 with the attention definition of Section 2):
+ *   for every cluster j of row b with representative r = rep_heads[b][j] >= 0
+ *       s[t]   = scale * sum_i q[b][r][i] * k_compact[b][j][t][i]    t < T
+ *       p_j[t] = exp(s[t] - max s) / sum_t exp(s[t] - max s)
+ *   for every head h, c = head_to_cluster[b][h]
+ *       out[b][h][:] = sum_t p_c[t] * v_cache[b][h][t][:]
+ * Long contexts are processed in token chunks whose partial softmax
+ * statistics and partial outputs are merged exactly; the result is the
+ * one-pass definition above up to fp32 rounding order.
+ *
+ *   q               [B,H,d]           only representatives' rows are read
+ *   k_compact       [B,k,Tc_cap,d]
+ *   v_cache         [B,H,T_cap,d]
+ *   head_to_cluster [B,H] int32, values in [0,k), pointing at used slots
+ *   rep_heads       [B,k] int32, head ids in [0,H) or -1 for unused slots
+ *   out             [B,H,d] fp32, written
+ *   probs_out       NULL, or [B,k,T] fp32: receives p_j (unused slots are
+ *                   not written); for tests and inspection
+ *   workspace       at least chai_decode_workspace_bytes(...) bytes, 256-byte
+ *                   aligned; contents need not be initialised and are
+ *                   undefined afterwards.  Two calls that run concurrently
+ *                   need separate workspaces.
+ * 1 <= T <= min(T_cap, Tc_cap), 1 <= k <= H, B >= 0 (B = 0 is a no-op).
+ */
+int chai_decode_attention(const void *q, const void *k_compact, const void *v_cache,
+                          const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H,
+                          int k, int T, int Tc_cap, int T_cap, int d, int dtype, float scale,
+                          float *out, float *probs_out, void *workspace, size_t workspace_bytes,
+                          void *stream);
+
+/*
+ * The two phases of chai_decode_attention as separate calls (same arguments,
+ * same workspace, same results): chai_decode_scores computes the scaled
+ * scores of every cluster and their per-chunk softmax statistics into the
+ * workspace (scores of Section 2, one per cluster as in Section 3.4);
+ * chai_decode_values turns them into probabilities and applies them to every
+ * head's own values (Section 3.5, Fig. 3).  chai_decode_values must follow
+ * chai_decode_scores on the same stream with the same sizes and workspace.
+ * Meant for callers that time or overlap the phases; chai_decode_attention
+ * is exactly the two in sequence.
+ */
+int chai_decode_scores(const void *q, const void *k_compact, const int32_t *rep_heads, int B, int H, int k,
+                       int T, int Tc_cap, int d, int dtype, float scale, void *workspace,
+                       size_t workspace_bytes, void *stream);
+int chai_decode_values(const void *v_cache, const int32_t *head_to_cluster, const int32_t *rep_heads, int B,
+                       int H, int k, int T, int T_cap, int d, int dtype, float *out, float *probs_out,
+                       void *workspace, size_t workspace_bytes, void *stream);
+
+/*
+ * Dense multi-head decode attention, the definition of Section 2
+ * (A_h = softmax(q_h K_h^T / sqrt(d)), y = A_0 V_0 (+) A_1 V_1 ...): the
+ * baseline clustered attention is compared against.  Runs the same kernels
+ * with every head its own cluster and K read in place.
+ *
+ *   q [B,H,d]; k_cache, v_cache [B,H,T_cap,d]; out [B,H,d] fp32
+ *   workspace: chai_decode_workspace_bytes(B,H,H,T,d,dtype) bytes.
+ */
+int chai_dense_decode_attention(const void *q, const void *k_cache, const void *v_cache, int B, int H,
+                                int T, int T_cap, int d, int dtype, float scale, float *out,
+                                void *workspace, size_t workspace_bytes, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHAI_H */

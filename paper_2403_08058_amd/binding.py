@@ -1,0 +1,205 @@
+"""Thin ctypes binding of libchai.so: argument marshalling only.
+
+Every function has the name and the argument order of its C entry point (see include/chai.h) and takes torch
+tensors that already live on the GPU; torch provides device memory and the current stream, nothing else.  All
+computation happens inside the HIP library.  There is no CPU fallback: if the library is missing, importing
+this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libchai.so")
+
+CHAI_OK = 0
+CHAI_F32, CHAI_BF16 = 0, 1
+STATUS_NAMES = {0: "CHAI_OK", 1: "CHAI_ERR_NULL", 2: "CHAI_ERR_SHAPE", 3: "CHAI_ERR_DTYPE", 4: "CHAI_ERR_WORKSPACE",
+                5: "CHAI_ERR_UNSUPPORTED", 6: "CHAI_ERR_HIP", 7: "CHAI_ERR_ALIGN"}
+
+EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_assign_clusters",
+           "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention",
+           "chai_decode_scores", "chai_decode_values", "chai_dense_decode_attention"]
+
+
+class ChaiError(RuntimeError):
+    def __init__(self, fn: str, status: int):
+        self.status = status
+        msg = _lib.chai_status_string(status).decode() if _lib is not None else "?"
+        super().__init__(f"{fn}: {STATUS_NAMES.get(status, status)} ({msg})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -m paper_2403_08058_amd.build` (there is no fallback path)")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, cf, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_int64, ctypes.c_size_t
+    L.chai_version.restype = ci
+    L.chai_status_string.restype = ctypes.c_char_p
+    L.chai_status_string.argtypes = [ci]
+    L.chai_score_features.argtypes = [vp, vp, ci, ci, ci, ci, ci, i64, i64, cf, vp, vp]
+    L.chai_assign_clusters.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp, vp]
+    L.chai_compact_kcache.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
+    L.chai_append_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
+    L.chai_decode_workspace_bytes.restype = sz
+    L.chai_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+    L.chai_decode_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, vp, sz, vp]
+    L.chai_dense_decode_attention.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
+    L.chai_decode_scores.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
+    L.chai_decode_values.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    for fn in EXPORTS:
+        if fn not in ("chai_status_string", "chai_decode_workspace_bytes"):
+            getattr(L, fn).restype = ci
+    return L
+
+
+_lib: Optional[ctypes.CDLL] = None
+_lib = _load()
+
+
+def lib() -> ctypes.CDLL:
+    return _lib
+
+
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return CHAI_F32
+    if t.dtype == torch.bfloat16:
+        return CHAI_BF16
+    raise TypeError(f"q/K/V must be float32 or bfloat16, got {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libchai takes device tensors")
+    if not t.is_contiguous():
+        raise ValueError("libchai takes contiguous tensors")
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _check(fn: str, status: int) -> None:
+    if status != CHAI_OK:
+        raise ChaiError(fn, status)
+
+
+def chai_version() -> int:
+    return int(_lib.chai_version())
+
+
+def chai_status_string(status: int) -> str:
+    return _lib.chai_status_string(int(status)).decode()
+
+
+def chai_score_features(q5, k5, n_tok: int, scale: float, feat=None, stream=None):
+    """q5 [B,H,nq,d], k5 [B,H,Tk,d] (nq, Tk >= n_tok; read in place) -> feat [B,H,n_tok*n_tok] fp32."""
+    B, H, nq, d = q5.shape
+    Tk = k5.shape[2]
+    if feat is None:
+        feat = torch.empty((B, H, n_tok * n_tok), dtype=torch.float32, device=q5.device)
+    _check("chai_score_features",
+           _lib.chai_score_features(_ptr(q5), _ptr(k5), B, H, n_tok, d, dtype_code(q5), nq * d, Tk * d, scale,
+                                    _ptr(feat), _stream(stream)))
+    return feat
+
+
+def chai_assign_clusters(feat, init_heads, max_iter: int = 50, head_to_cluster=None, rep_heads=None, n_clusters=None,
+                         iters=None, stream=None):
+    """feat [B,H,F] fp32, init_heads [B,k] int32 -> (head_to_cluster [B,H], rep_heads [B,k], n_clusters [B], iters [B])."""
+    B, H, F = feat.shape
+    k = init_heads.shape[1]
+    dev = feat.device
+    head_to_cluster = torch.empty((B, H), dtype=torch.int32, device=dev) if head_to_cluster is None else head_to_cluster
+    rep_heads = torch.empty((B, k), dtype=torch.int32, device=dev) if rep_heads is None else rep_heads
+    n_clusters = torch.empty((B,), dtype=torch.int32, device=dev) if n_clusters is None else n_clusters
+    iters = torch.empty((B,), dtype=torch.int32, device=dev) if iters is None else iters
+    _check("chai_assign_clusters",
+           _lib.chai_assign_clusters(_ptr(feat), B, H, F, k, _ptr(init_heads), max_iter, _ptr(head_to_cluster),
+                                     _ptr(rep_heads), _ptr(n_clusters), _ptr(iters), _stream(stream)))
+    return head_to_cluster, rep_heads, n_clusters, iters
+
+
+def chai_compact_kcache(k_full, rep_heads, k_compact, T: int, stream=None):
+    """k_full [B,H,T_cap,d], rep_heads [B,k] -> first T rows of k_compact [B,k,Tc_cap,d]."""
+    B, H, T_cap, d = k_full.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    _check("chai_compact_kcache",
+           _lib.chai_compact_kcache(_ptr(k_full), _ptr(rep_heads), _ptr(k_compact), B, H, k, T, T_cap, Tc_cap, d,
+                                    dtype_code(k_full), _stream(stream)))
+    return k_compact
+
+
+def chai_append_kv(k_new, v_new, rep_heads, k_compact, v_cache, pos: int, stream=None):
+    B, H, d = k_new.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    T_cap = v_cache.shape[2]
+    _check("chai_append_kv",
+           _lib.chai_append_kv(_ptr(k_new), _ptr(v_new), _ptr(rep_heads), _ptr(k_compact), _ptr(v_cache), B, H, k, pos,
+                               Tc_cap, T_cap, d, dtype_code(k_new), _stream(stream)))
+
+
+def chai_decode_workspace_bytes(B: int, H: int, k: int, T: int, d: int, dtype: int) -> int:
+    return int(_lib.chai_decode_workspace_bytes(B, H, k, T, d, dtype))
+
+
+def chai_decode_attention(q, k_compact, v_cache, head_to_cluster, rep_heads, T: int, scale: float, out, workspace,
+                          probs_out=None, stream=None):
+    """One clustered decode step of one layer; `out` [B,H,d] fp32 and `workspace` (uint8) are caller-provided."""
+    B, H, d = q.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    T_cap = v_cache.shape[2]
+    _check("chai_decode_attention",
+           _lib.chai_decode_attention(_ptr(q), _ptr(k_compact), _ptr(v_cache), _ptr(head_to_cluster), _ptr(rep_heads),
+                                      B, H, k, T, Tc_cap, T_cap, d, dtype_code(q), scale, _ptr(out), _ptr(probs_out),
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                      _stream(stream)))
+    return out
+
+
+def chai_decode_scores(q, k_compact, rep_heads, T: int, scale: float, workspace, stream=None):
+    """First phase of chai_decode_attention: scores and chunk statistics of every cluster into the workspace."""
+    B, H, d = q.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    _check("chai_decode_scores",
+           _lib.chai_decode_scores(_ptr(q), _ptr(k_compact), _ptr(rep_heads), B, H, k, T, Tc_cap, d, dtype_code(q),
+                                   scale, _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                   _stream(stream)))
+
+
+def chai_decode_values(v_cache, head_to_cluster, rep_heads, T: int, out, workspace, probs_out=None, stream=None):
+    """Second phase of chai_decode_attention: probabilities from the workspace applied to every head's values."""
+    B, H, T_cap, d = v_cache.shape
+    k = rep_heads.shape[1]
+    _check("chai_decode_values",
+           _lib.chai_decode_values(_ptr(v_cache), _ptr(head_to_cluster), _ptr(rep_heads), B, H, k, T, T_cap, d,
+                                   dtype_code(v_cache), _ptr(out), _ptr(probs_out), _ptr(workspace),
+                                   workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out
+
+
+def chai_dense_decode_attention(q, k_cache, v_cache, T: int, scale: float, out, workspace, stream=None):
+    B, H, d = q.shape
+    T_cap = k_cache.shape[2]
+    _check("chai_dense_decode_attention",
+           _lib.chai_dense_decode_attention(_ptr(q), _ptr(k_cache), _ptr(v_cache), B, H, T, T_cap, d, dtype_code(q),
+                                            scale, _ptr(out), _ptr(workspace),
+                                            workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out
+
+
+def alloc_workspace(B: int, H: int, k: int, T: int, d: int, dtype: int, device="cuda") -> torch.Tensor:
+    """Device scratch of the size the decode calls ask for (torch allocations are 512-byte aligned)."""
+    n = max(chai_decode_workspace_bytes(B, H, k, T, d, dtype), 256)
+    return torch.empty((n,), dtype=torch.uint8, device=device)

@@ -1,0 +1,191 @@
+// extern "C" entry points of libchai.so: host-side argument checks, then kernel launches.  Nothing here
+// allocates, synchronises or reads device memory.
+#include "chai_internal.h"
+
+using namespace chai;
+
+namespace {
+
+constexpr int kVersion = 100;
+constexpr int kMaxGridYZ = 65535;
+
+inline bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+inline bool bad_dtype(int dtype) { return dtype != CHAI_F32 && dtype != CHAI_BF16; }
+inline int hip_status(int e) { return e == (int)hipSuccess ? CHAI_OK : CHAI_ERR_HIP; }
+
+// size checks common to every decode entry point; fills the launch plan
+int check_sizes(int B, int H, int k, int T, int Tc_cap, int T_cap, int d, int dtype, const void *workspace,
+                size_t workspace_bytes, DecodePlan *plan)
+{
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || k < 1 || k > H || T < 1 || T > T_cap || T > Tc_cap || d < 1) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || B > kMaxGridYZ || H > kMaxGridYZ) return CHAI_ERR_UNSUPPORTED;
+    *plan = make_decode_plan(B, H, k, T);
+    if (B > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < plan->bytes))
+        return CHAI_ERR_WORKSPACE;
+    return CHAI_OK;
+}
+
+int check_scores(const void *q, const void *kc, int B, int H, int k, int T, int Tc_cap, int d, int dtype,
+                 const void *workspace, size_t workspace_bytes, DecodePlan *plan)
+{
+    if (!q || !kc) return CHAI_ERR_NULL;
+    const int st = check_sizes(B, H, k, T, Tc_cap, T, d, dtype, workspace, workspace_bytes, plan);
+    if (st != CHAI_OK && st != CHAI_ERR_WORKSPACE) return st;
+    if (!aligned16(q) || !aligned16(kc)) return CHAI_ERR_ALIGN;
+    return st;
+}
+
+int check_values(const void *v, const float *out, int B, int H, int k, int T, int T_cap, int d, int dtype,
+                 const void *workspace, size_t workspace_bytes, DecodePlan *plan)
+{
+    if (!v || !out) return CHAI_ERR_NULL;
+    const int st = check_sizes(B, H, k, T, T, T_cap, d, dtype, workspace, workspace_bytes, plan);
+    if (st != CHAI_OK && st != CHAI_ERR_WORKSPACE) return st;
+    if (!aligned16(v) || !aligned16(out)) return CHAI_ERR_ALIGN;
+    return st;
+}
+
+}  // namespace
+
+extern "C" {
+
+int chai_version(void) { return kVersion; }
+
+const char *chai_status_string(int status)
+{
+    switch (status) {
+    case CHAI_OK: return "ok";
+    case CHAI_ERR_NULL: return "a required pointer is NULL";
+    case CHAI_ERR_SHAPE: return "a size is out of range or inconsistent";
+    case CHAI_ERR_DTYPE: return "unknown dtype";
+    case CHAI_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case CHAI_ERR_UNSUPPORTED: return "sizes not supported by this build";
+    case CHAI_ERR_HIP: return "HIP runtime error at kernel launch";
+    case CHAI_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    default: return "unknown status";
+    }
+}
+
+int chai_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int d, int dtype,
+                        int64_t q_head_stride, int64_t k_head_stride, float scale, float *feat, void *stream)
+{
+    if (!q5 || !k5 || !feat) return CHAI_ERR_NULL;
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || n_tok < 1 || d < 1) return CHAI_ERR_SHAPE;
+    if (q_head_stride < (int64_t)n_tok * d || k_head_stride < (int64_t)n_tok * d) return CHAI_ERR_SHAPE;
+    if ((q_head_stride & 7) || (k_head_stride & 7)) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || n_tok > 8 || B > kMaxGridYZ) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(q5) || !aligned16(k5)) return CHAI_ERR_ALIGN;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_score_features(q5, k5, B, H, n_tok, dtype, q_head_stride, k_head_stride, scale, feat,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+int chai_assign_clusters(const float *feat, int B, int H, int F, int k, const int32_t *init_heads, int max_iter,
+                         int32_t *head_to_cluster, int32_t *rep_heads, int32_t *n_clusters, int32_t *iters,
+                         void *stream)
+{
+    if (!feat || !init_heads || !head_to_cluster || !rep_heads || !n_clusters) return CHAI_ERR_NULL;
+    if (B < 0 || H < 1 || F < 1 || k < 1 || k > H || max_iter < 1) return CHAI_ERR_SHAPE;
+    if (H > 256 || F > 64 || (long long)k * F > 7168) return CHAI_ERR_UNSUPPORTED;
+    if (assign_clusters_lds_bytes(H, F, k) > 64 * 1024 - 64) return CHAI_ERR_UNSUPPORTED;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_assign_clusters(feat, B, H, F, k, init_heads, max_iter, head_to_cluster, rep_heads,
+                                             n_clusters, iters, static_cast<hipStream_t>(stream)));
+}
+
+int chai_compact_kcache(const void *k_full, const int32_t *rep_heads, void *k_compact, int B, int H, int k, int T,
+                        int T_cap, int Tc_cap, int d, int dtype, void *stream)
+{
+    if (!k_full || !rep_heads || !k_compact) return CHAI_ERR_NULL;
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || k < 1 || k > H || T < 0 || T > T_cap || T > Tc_cap || d < 1) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || B > kMaxGridYZ || k > kMaxGridYZ) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(k_full) || !aligned16(k_compact)) return CHAI_ERR_ALIGN;
+    if (B == 0 || T == 0) return CHAI_OK;
+    return hip_status(launch_compact_kcache(k_full, rep_heads, k_compact, B, H, k, T, T_cap, Tc_cap, dtype,
+                                            static_cast<hipStream_t>(stream)));
+}
+
+int chai_append_kv(const void *k_new, const void *v_new, const int32_t *rep_heads, void *k_compact, void *v_cache,
+                   int B, int H, int k, int pos, int Tc_cap, int T_cap, int d, int dtype, void *stream)
+{
+    if (!k_new || !v_new || !rep_heads || !k_compact || !v_cache) return CHAI_ERR_NULL;
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || k < 1 || k > H || pos < 0 || pos >= T_cap || pos >= Tc_cap || d < 1) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || B > kMaxGridYZ) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_compact) || !aligned16(v_cache)) return CHAI_ERR_ALIGN;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_append_kv(k_new, v_new, rep_heads, k_compact, v_cache, B, H, k, pos, Tc_cap, T_cap,
+                                       dtype, static_cast<hipStream_t>(stream)));
+}
+
+size_t chai_decode_workspace_bytes(int B, int H, int k, int T, int d, int dtype)
+{
+    if (B < 0 || H < 1 || k < 1 || k > H || T < 1 || d != kHeadDim || bad_dtype(dtype)) return 0;
+    if (B == 0) return 256;
+    return make_decode_plan(B, H, k, T).bytes;
+}
+
+int chai_decode_scores(const void *q, const void *k_compact, const int32_t *rep_heads, int B, int H, int k, int T,
+                       int Tc_cap, int d, int dtype, float scale, void *workspace, size_t workspace_bytes,
+                       void *stream)
+{
+    if (!rep_heads) return CHAI_ERR_NULL;
+    DecodePlan plan;
+    const int st = check_scores(q, k_compact, B, H, k, T, Tc_cap, d, dtype, workspace, workspace_bytes, &plan);
+    if (st != CHAI_OK) return st;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_scores(q, k_compact, rep_heads, B, H, k, T, Tc_cap, dtype, scale, workspace, plan, false,
+                                    static_cast<hipStream_t>(stream)));
+}
+
+int chai_decode_values(const void *v_cache, const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H,
+                       int k, int T, int T_cap, int d, int dtype, float *out, float *probs_out, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    if (!head_to_cluster || !rep_heads) return CHAI_ERR_NULL;
+    DecodePlan plan;
+    const int st = check_values(v_cache, out, B, H, k, T, T_cap, d, dtype, workspace, workspace_bytes, &plan);
+    if (st != CHAI_OK) return st;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_values(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, dtype, out, probs_out,
+                                    workspace, plan, false, static_cast<hipStream_t>(stream)));
+}
+
+int chai_decode_attention(const void *q, const void *k_compact, const void *v_cache, const int32_t *head_to_cluster,
+                          const int32_t *rep_heads, int B, int H, int k, int T, int Tc_cap, int T_cap, int d,
+                          int dtype, float scale, float *out, float *probs_out, void *workspace,
+                          size_t workspace_bytes, void *stream)
+{
+    if (!head_to_cluster || !rep_heads) return CHAI_ERR_NULL;
+    DecodePlan plan;
+    int st = check_scores(q, k_compact, B, H, k, T, Tc_cap, d, dtype, workspace, workspace_bytes, &plan);
+    if (st == CHAI_OK) st = check_values(v_cache, out, B, H, k, T, T_cap, d, dtype, workspace, workspace_bytes, &plan);
+    if (st != CHAI_OK) return st;
+    if (B == 0) return CHAI_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = hip_status(launch_scores(q, k_compact, rep_heads, B, H, k, T, Tc_cap, dtype, scale, workspace, plan, false, s));
+    if (st != CHAI_OK) return st;
+    return hip_status(launch_values(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, dtype, out, probs_out,
+                                    workspace, plan, false, s));
+}
+
+int chai_dense_decode_attention(const void *q, const void *k_cache, const void *v_cache, int B, int H, int T,
+                                int T_cap, int d, int dtype, float scale, float *out, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    DecodePlan plan;
+    int st = check_scores(q, k_cache, B, H, H, T, T_cap, d, dtype, workspace, workspace_bytes, &plan);
+    if (st == CHAI_OK) st = check_values(v_cache, out, B, H, H, T, T_cap, d, dtype, workspace, workspace_bytes, &plan);
+    if (st != CHAI_OK) return st;
+    if (B == 0) return CHAI_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = hip_status(launch_scores(q, k_cache, nullptr, B, H, H, T, T_cap, dtype, scale, workspace, plan, true, s));
+    if (st != CHAI_OK) return st;
+    return hip_status(launch_values(v_cache, nullptr, nullptr, B, H, H, T, T_cap, dtype, out, nullptr, workspace, plan,
+                                    true, s));
+}
+
+}  // extern "C"

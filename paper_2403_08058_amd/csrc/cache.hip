@@ -1,0 +1,87 @@
+// K-cache pruning and cache growth (Section 3.5: after membership is fixed only the representatives' keys are
+// kept; all values are kept).  Pure 16-byte copies: bit-exact by construction, bound by HBM bandwidth.
+#include "chai_internal.h"
+
+namespace chai {
+
+namespace {
+
+constexpr int kCopyUnroll = 4;
+
+// grid (ceil(vec_per_stream / (256*4)), k, B): copies the first T rows of the representative's key stream.
+__global__ __launch_bounds__(kBlock) void compact_kernel(const uint4 *__restrict__ k_full,
+                                                         const int32_t *__restrict__ rep,
+                                                         uint4 *__restrict__ k_compact, int H, int k,
+                                                         long long vec_per_stream, long long src_stride,
+                                                         long long dst_stride)
+{
+    const int j = blockIdx.y, b = blockIdx.z;
+    int r = rep[(size_t)b * k + j];
+    if (r < 0) return;
+    r = min(r, H - 1);
+    const uint4 *src = k_full + ((size_t)b * H + r) * src_stride;
+    uint4 *dst = k_compact + ((size_t)b * k + j) * dst_stride;
+    const long long base = ((long long)blockIdx.x * kCopyUnroll) * kBlock + threadIdx.x;
+    uint4 tmp[kCopyUnroll];
+#pragma unroll
+    for (int u = 0; u < kCopyUnroll; ++u) {
+        const long long i = base + (long long)u * kBlock;
+        if (i < vec_per_stream) tmp[u] = src[i];
+    }
+#pragma unroll
+    for (int u = 0; u < kCopyUnroll; ++u) {
+        const long long i = base + (long long)u * kBlock;
+        if (i < vec_per_stream) dst[i] = tmp[u];
+    }
+}
+
+// grid (k + H, B), one wave: rows 0..k-1 are key rows of the representatives, rows k..k+H-1 are value rows.
+__global__ __launch_bounds__(64) void append_kernel(const uint4 *__restrict__ k_new, const uint4 *__restrict__ v_new,
+                                                    const int32_t *__restrict__ rep, uint4 *__restrict__ k_compact,
+                                                    uint4 *__restrict__ v_cache, int H, int k, int pos,
+                                                    long long kc_stride, long long v_stride, int vec_per_row)
+{
+    const int row = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    if (lane >= vec_per_row) return;
+    if (row < k) {
+        int r = rep[(size_t)b * k + row];
+        if (r < 0) return;
+        r = min(r, H - 1);
+        k_compact[((size_t)b * k + row) * kc_stride + (size_t)pos * vec_per_row + lane] =
+            k_new[((size_t)b * H + r) * vec_per_row + lane];
+    } else {
+        const int h = row - k;
+        v_cache[((size_t)b * H + h) * v_stride + (size_t)pos * vec_per_row + lane] =
+            v_new[((size_t)b * H + h) * vec_per_row + lane];
+    }
+}
+
+}  // namespace
+
+int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
+                          int T_cap, int Tc_cap, int dtype, hipStream_t stream)
+{
+    const long long vec_per_row = kHeadDim * (dtype == CHAI_BF16 ? 2 : 4) / 16;
+    const long long vec_per_stream = (long long)T * vec_per_row;
+    const long long per_block = (long long)kBlock * kCopyUnroll;
+    const unsigned int gx = (unsigned int)((vec_per_stream + per_block - 1) / per_block);
+    compact_kernel<<<dim3(gx, k, B), kBlock, 0, stream>>>(static_cast<const uint4 *>(k_full), rep,
+                                                          static_cast<uint4 *>(k_compact), H, k, vec_per_stream,
+                                                          (long long)T_cap * vec_per_row,
+                                                          (long long)Tc_cap * vec_per_row);
+    return (int)hipGetLastError();
+}
+
+int launch_append_kv(const void *k_new, const void *v_new, const int32_t *rep, void *k_compact, void *v_cache, int B,
+                     int H, int k, int pos, int Tc_cap, int T_cap, int dtype, hipStream_t stream)
+{
+    const int vec_per_row = kHeadDim * (dtype == CHAI_BF16 ? 2 : 4) / 16;
+    append_kernel<<<dim3(k + H, B), 64, 0, stream>>>(static_cast<const uint4 *>(k_new),
+                                                     static_cast<const uint4 *>(v_new), rep,
+                                                     static_cast<uint4 *>(k_compact), static_cast<uint4 *>(v_cache),
+                                                     H, k, pos, (long long)Tc_cap * vec_per_row,
+                                                     (long long)T_cap * vec_per_row, vec_per_row);
+    return (int)hipGetLastError();
+}
+
+}  // namespace chai

@@ -1,0 +1,49 @@
+// Internal declarations shared by the translation units of libchai.so (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "chai.h"
+
+namespace chai {
+
+constexpr int kHeadDim = 128;       // the only head dimension the kernels are written for
+constexpr int kBlock = 256;         // threads per workgroup of the streaming kernels (4 wave64)
+
+// How one decode call is cut into workgroups.  Derived from the sizes alone, so the workspace query and the
+// call itself always agree.
+struct DecodePlan {
+    int cs;          // tokens per workgroup of the score kernel (one softmax-statistics record each)
+    int n_cs;        // score chunks per (b, cluster) = ceil(T / cs)
+    int cp;          // tokens per workgroup of the value kernel
+    int n_cp;        // value chunks per (b, head) = ceil(T / cp)
+    size_t off_scores, off_stats, off_partial, off_counter, bytes;
+};
+
+DecodePlan make_decode_plan(int B, int H, int k, int T);
+
+// Enqueue the two kernels of one decode call.  identity = true: every head is its own cluster and the maps
+// are not read (dense attention).  Each returns a hipError_t as int.
+int launch_scores(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap,
+                  int dtype, float scale, void *workspace, const DecodePlan &plan, bool identity,
+                  hipStream_t stream);
+int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
+                  int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
+                  hipStream_t stream);
+
+int launch_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int dtype, int64_t qs,
+                          int64_t ks, float scale, float *feat, hipStream_t stream);
+
+int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const int32_t *init_heads, int max_iter,
+                           int32_t *h2c, int32_t *rep, int32_t *ncl, int32_t *iters, hipStream_t stream);
+size_t assign_clusters_lds_bytes(int H, int F, int k);
+
+int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
+                          int T_cap, int Tc_cap, int dtype, hipStream_t stream);
+
+int launch_append_kv(const void *k_new, const void *v_new, const int32_t *rep, void *k_compact, void *v_cache, int B,
+                     int H, int k, int pos, int Tc_cap, int T_cap, int dtype, hipStream_t stream);
+
+}  // namespace chai

@@ -1,0 +1,197 @@
+// Cluster-membership kernels: the 5-token attention-score features (Section 3.3, with f(Q,K) = softmax(Q K^T)
+// of Section 3.1) and K-Means over them (Section 3.5; clustering error of Section 3.2).
+//
+// The k-means result must be bit-identical to the sequential statement of the algorithm for the same feature
+// bits, so every fp64 multiply, add, subtract and divide below is rounded on its own: this file is compiled
+// with -ffp-contract=off, the pragma repeats it, and each sum runs in the stated index order inside ONE
+// thread (threads split independent sums, never one sum).
+#include "chai_internal.h"
+
+#pragma clang fp contract(off)
+
+namespace chai {
+
+namespace {
+
+__device__ __forceinline__ double load_elem(const void *base, size_t idx, bool bf16)
+{
+    if (bf16) {
+        const unsigned int w = (unsigned int)static_cast<const unsigned short *>(base)[idx] << 16;
+        return (double)__uint_as_float(w);
+    }
+    return (double)static_cast<const float *>(base)[idx];
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Features: grid (H, B), one wave per head.  Lane p < n_tok*(n_tok+1)/2 owns one causal (i, j) pair and runs
+// its 128-term dot product in element order in fp64; lane i < n_tok then normalises row i.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(64) void feature_kernel(const void *__restrict__ q5, const void *__restrict__ k5,
+                                                     int H, int n_tok, int bf16, long long qs, long long ks,
+                                                     double scale, float *__restrict__ feat)
+{
+    __shared__ double s[8][8];
+    const int h = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    const size_t head = (size_t)b * H + h;
+
+    // lane -> (i, j) with j <= i, row by row
+    int i = 0, j = lane;
+    while (i < n_tok && j > i) { j -= i + 1; ++i; }
+    if (i < n_tok) {
+        const size_t qo = head * (size_t)qs + (size_t)i * kHeadDim;
+        const size_t ko = head * (size_t)ks + (size_t)j * kHeadDim;
+        double acc = 0.0;
+        for (int c = 0; c < kHeadDim; ++c) {
+            const double prod = load_elem(q5, qo + c, bf16) * load_elem(k5, ko + c, bf16);
+            acc = acc + prod;
+        }
+        s[i][j] = scale * acc;
+    }
+    __syncthreads();
+    if (lane < n_tok) {
+        const int row = lane;
+        double m = s[row][0];
+        for (int c = 1; c <= row; ++c) m = fmax(m, s[row][c]);
+        double e[8];
+        double z = 0.0;
+        for (int c = 0; c <= row; ++c) { e[c] = exp(s[row][c] - m); z = z + e[c]; }
+        float *f = feat + head * (size_t)(n_tok * n_tok) + (size_t)row * n_tok;
+        for (int c = 0; c < n_tok; ++c) f[c] = c <= row ? (float)(e[c] / z) : 0.0f;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// K-Means: grid (B), one workgroup of 256 threads per batch row.  Dynamic LDS: centres [k][F] fp64, then
+// per-head distance [H] fp64, assignment/previous assignment [H], counts/labels [k].
+// ---------------------------------------------------------------------------------------------------------
+__device__ __forceinline__ double sqdist(const float *__restrict__ x, const double *c, int F)
+{
+    double acc = 0.0;
+    for (int f = 0; f < F; ++f) {
+        const double diff = (double)x[f] - c[f];
+        const double sq = diff * diff;
+        acc = acc + sq;
+    }
+    return acc;
+}
+
+__global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict__ feat, int H, int F, int k,
+                                                        const int32_t *__restrict__ init_heads, int max_iter,
+                                                        int32_t *__restrict__ h2c, int32_t *__restrict__ rep,
+                                                        int32_t *__restrict__ ncl, int32_t *__restrict__ iters)
+{
+    extern __shared__ double lds[];
+    double *centre = lds;                       // [k*F]
+    double *dmin = centre + (size_t)k * F;      // [H]
+    int *assign = reinterpret_cast<int *>(dmin + H);   // [H]
+    int *prev = assign + H;                     // [H]
+    int *count = prev + H;                      // [k]
+    int *label = count + k;                     // [k]
+    __shared__ int changed;
+
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const float *X = feat + (size_t)b * H * F;
+
+    for (int i = tid; i < k * F; i += kBlock) {
+        const int j = i / F, f = i - j * F;
+        const int h0 = min(max(init_heads[(size_t)b * k + j], 0), H - 1);
+        centre[i] = (double)X[(size_t)h0 * F + f];
+    }
+    for (int h = tid; h < H; h += kBlock) prev[h] = -1;
+    __syncthreads();
+
+    int it = 0;
+    for (;;) {
+        ++it;
+        // assignment: one thread per head, centres in ascending order, strict '<' keeps the lowest on ties
+        for (int h = tid; h < H; h += kBlock) {
+            const float *x = X + (size_t)h * F;
+            int best = 0;
+            double bd = sqdist(x, centre, F);
+            for (int j = 1; j < k; ++j) {
+                const double dj = sqdist(x, centre + (size_t)j * F, F);
+                if (dj < bd) { bd = dj; best = j; }
+            }
+            assign[h] = best;
+            dmin[h] = bd;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            for (int j = 0; j < k; ++j) count[j] = 0;
+            for (int h = 0; h < H; ++h) count[assign[h]]++;
+            // repair of centres that received no head, in ascending order
+            for (int j = 0; j < k; ++j) {
+                if (count[j] != 0) continue;
+                int pick = -1;
+                double far = 0.0;
+                for (int h = 0; h < H; ++h)
+                    if (count[assign[h]] >= 2 && dmin[h] > far) { far = dmin[h]; pick = h; }
+                if (pick < 0) continue;
+                count[assign[pick]]--;
+                assign[pick] = j;
+                count[j] = 1;
+                dmin[pick] = 0.0;
+            }
+            int ch = 0;
+            for (int h = 0; h < H; ++h) {
+                if (assign[h] != prev[h]) ch = 1;
+                prev[h] = assign[h];
+            }
+            changed = ch;
+        }
+        __syncthreads();
+        if (!changed || it >= max_iter) break;      // same value in every thread
+        // update: one thread per (centre, coordinate), members added in head order
+        for (int i = tid; i < k * F; i += kBlock) {
+            const int j = i / F, f = i - j * F;
+            if (count[j] == 0) continue;
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h)
+                if (assign[h] == j) acc = acc + (double)X[(size_t)h * F + f];
+            centre[i] = acc / (double)count[j];
+        }
+        __syncthreads();
+    }
+
+    // canonical labels: clusters numbered by their lowest member, which represents them
+    if (tid == 0) {
+        for (int j = 0; j < k; ++j) { label[j] = -1; rep[(size_t)b * k + j] = -1; }
+        int n = 0;
+        for (int h = 0; h < H; ++h) {
+            const int a = assign[h];
+            if (label[a] < 0) {
+                label[a] = n;
+                rep[(size_t)b * k + n] = h;
+                ++n;
+            }
+            h2c[(size_t)b * H + h] = label[a];
+        }
+        ncl[b] = n;
+        if (iters) iters[b] = it;
+    }
+}
+
+}  // namespace
+
+int launch_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int dtype, int64_t qs, int64_t ks,
+                          float scale, float *feat, hipStream_t stream)
+{
+    feature_kernel<<<dim3(H, B), 64, 0, stream>>>(q5, k5, H, n_tok, dtype == CHAI_BF16 ? 1 : 0, (long long)qs,
+                                                  (long long)ks, (double)scale, feat);
+    return (int)hipGetLastError();
+}
+
+size_t assign_clusters_lds_bytes(int H, int F, int k)
+{
+    return sizeof(double) * ((size_t)k * F + H) + sizeof(int) * (2 * (size_t)H + 2 * (size_t)k);
+}
+
+int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const int32_t *init_heads, int max_iter,
+                           int32_t *h2c, int32_t *rep, int32_t *ncl, int32_t *iters, hipStream_t stream)
+{
+    kmeans_kernel<<<dim3(B), kBlock, assign_clusters_lds_bytes(H, F, k), stream>>>(feat, H, F, k, init_heads,
+                                                                                  max_iter, h2c, rep, ncl, iters);
+    return (int)hipGetLastError();
+}
+
+}  // namespace chai

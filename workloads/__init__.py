@@ -138,7 +138,8 @@ def rng(seed: int, layer: int, tag: str, extra: int = 0) -> np.random.Generator:
     return np.random.Generator(np.random.Philox(key=key))
 
 
-def _store(x: np.ndarray, dtype: int) -> np.ndarray:
+def store(x: np.ndarray, dtype: int) -> np.ndarray:
+    """fp32 values -> storage type (fp32 unchanged, or bf16 bit patterns)."""
     x = np.ascontiguousarray(x, np.float32)
     return x if dtype == F32 else f32_to_bf16_bits(x)
 
@@ -147,7 +148,7 @@ def normal(g: np.random.Generator, shape: Sequence[int], dtype: int, sigma: floa
     x = g.standard_normal(size=tuple(shape), dtype=np.float32)
     if sigma != 1.0:
         x *= np.float32(sigma)
-    return _store(x, dtype)
+    return store(x, dtype)
 
 
 def random_membership(g: np.random.Generator, B: int, H: int, k: int) -> Tuple[np.ndarray, np.ndarray]:
@@ -217,7 +218,7 @@ def centroid_plus_noise(g_cent: np.random.Generator, g_noise: np.random.Generato
     for b in range(B):
         x[b] = cent[b, groups[b]]
     x += np.float32(sigma) * g_noise.standard_normal(size=(B, H, rows, d), dtype=np.float32)
-    return _store(x, dtype)
+    return store(x, dtype)
 
 
 @dataclasses.dataclass
