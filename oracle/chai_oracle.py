@@ -88,6 +88,11 @@ def _p(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 
 
+def _f32(scale) -> float:
+    """The attention scale is an fp32 quantity (the device ABI takes a float): both sides use the same value."""
+    return float(np.float32(scale))
+
+
 def _check(rc: int, what: str) -> None:
     if rc != 0:
         raise ValueError(f"{what}: oracle rejected the arguments (code {rc})")
@@ -108,7 +113,7 @@ def clustered_decode(q, k_full, v, head_to_cluster, rep_heads, T, scale, want_pr
     out = np.empty((B, H, d), np.float64)
     probs = np.empty((B, k, T), np.float64) if want_probs else None
     rc = lib().chai_oracle_clustered_decode(_p(q), _p(k_full), _p(v), _p(h2c), _p(rep), B, H, k, T, T_cap, d, dt,
-                                            float(scale), _p(out), _p(probs))
+                                            _f32(scale), _p(out), _p(probs))
     _check(rc, "clustered_decode")
     return (out, probs) if want_probs else out
 
@@ -122,7 +127,7 @@ def dense_decode(q, k_cache, v, T, scale, want_probs=False):
     assert k_cache.shape == (B, H, T_cap, d) and v.shape == (B, H, T_cap, d)
     out = np.empty((B, H, d), np.float64)
     probs = np.empty((B, H, T), np.float64) if want_probs else None
-    rc = lib().chai_oracle_dense_decode(_p(q), _p(k_cache), _p(v), B, H, T, T_cap, d, dt, float(scale), _p(out),
+    rc = lib().chai_oracle_dense_decode(_p(q), _p(k_cache), _p(v), B, H, T, T_cap, d, dt, _f32(scale), _p(out),
                                         _p(probs))
     _check(rc, "dense_decode")
     return (out, probs) if want_probs else out
@@ -138,7 +143,7 @@ def score_features(q5, k5, scale, n_tok=None):
     assert k5.shape[:2] == (B, H) and k5.shape[3] == d and k5.shape[2] >= n_tok and nq >= n_tok
     feat = np.empty((B, H, n_tok * n_tok), np.float32)
     rc = lib().chai_oracle_score_features(_p(q5), _p(k5), B, H, n_tok, d, dt, nq * d, k5.shape[2] * d,
-                                          float(scale), _p(feat))
+                                          _f32(scale), _p(feat))
     _check(rc, "score_features")
     return feat
 

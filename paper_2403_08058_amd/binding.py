@@ -33,11 +33,11 @@ class ChaiError(RuntimeError):
         super().__init__(f"{fn}: {STATUS_NAMES.get(status, status)} ({msg})")
 
 
-def _load() -> ctypes.CDLL:
-    if not os.path.exists(LIB_PATH):
+def _load(path: str = LIB_PATH) -> ctypes.CDLL:
+    if not os.path.exists(path):
         raise ImportError(
-            f"{LIB_PATH} is not built; run `python -m paper_2403_08058_amd.build` (there is no fallback path)")
-    L = ctypes.CDLL(LIB_PATH)
+            f"{path} is not built; run `python -m paper_2403_08058_amd.build` (there is no fallback path)")
+    L = ctypes.CDLL(path)
     vp, ci, cf, i64, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_int64, ctypes.c_size_t
     L.chai_version.restype = ci
     L.chai_status_string.restype = ctypes.c_char_p

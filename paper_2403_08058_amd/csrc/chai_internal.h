@@ -19,7 +19,7 @@ struct DecodePlan {
     int n_cs;        // score chunks per (b, cluster) = ceil(T / cs)
     int cp;          // tokens per workgroup of the value kernel
     int n_cp;        // value chunks per (b, head) = ceil(T / cp)
-    size_t off_scores, off_stats, off_partial, off_counter, bytes;
+    size_t off_scores, off_stats, off_partial, bytes;
 };
 
 DecodePlan make_decode_plan(int B, int H, int k, int T);

@@ -1,30 +1,37 @@
 // Clustered-head decode attention for gfx950 (MI355X): the score kernel streams the compact K cache once per
 // cluster, the value kernel streams the full V cache once per head.  Both are HBM-bandwidth kernels: every
-// lane issues 16-byte loads, 16 lanes (bf16) or 32 lanes (fp32) cover one 128-element row, a wave64 load
-// instruction covers 1 KiB of consecutive rows, and the four waves of a workgroup walk a contiguous region.
+// lane issues 16-byte non-temporal loads, 16 lanes (bf16) or 32 lanes (fp32) cover one 128-element row, a
+// wave64 load instruction covers 1 KiB of consecutive rows, a wave keeps 8 KiB (one batch) or more in flight
+// and the four waves of a workgroup walk neighbouring batches of one contiguous region.
 //
 // Method: attention definition of Section 2; one score computation per cluster with the representative's
 // query and keys, shared by the member heads, each applying it to its own values (Sections 3.4-3.5, Fig. 3).
 #include "chai_internal.h"
 
+#ifdef CHAI_TUNING
+#include <cstdlib>
+#endif
+
 namespace chai {
 
 namespace {
 
-constexpr int kUnroll = 8;        // independent 16-byte loads in flight per lane
+constexpr int kUnroll = 8;        // 16-byte loads per lane in one batch
 constexpr int kMaxCs = 256;       // largest score chunk (= workgroup size: one thread per score)
-constexpr int kMaxCp = 1024;      // largest value chunk (probabilities staged in LDS)
+constexpr int kWaves = kBlock / 64;
 
 template <bool BF16>
 struct Tile {
     static constexpr int EPL = BF16 ? 8 : 4;               // elements per lane per load (16 bytes)
     static constexpr int LPR = kHeadDim / EPL;             // lanes per row: 16 (bf16) / 32 (fp32)
     static constexpr int RPW = 64 / LPR;                   // rows per wave load: 4 / 2
-    static constexpr int RPB = RPW * (kBlock / 64);        // rows per workgroup iteration: 16 / 8
+    static constexpr int BATCH = RPW * kUnroll;            // rows per wave batch: 32 / 16
     static constexpr int ROW_BYTES = kHeadDim * (BF16 ? 2 : 4);
 };
 
-__device__ __forceinline__ void unpack(const uint4 &raw, float (&f)[8])
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void unpack(const u32x4 &raw, float (&f)[8])
 {
     // bf16 pairs: the low half-word is the even element; a bf16 is the top half of an fp32
     f[0] = __uint_as_float(raw.x << 16); f[1] = __uint_as_float(raw.x & 0xffff0000u);
@@ -33,15 +40,17 @@ __device__ __forceinline__ void unpack(const uint4 &raw, float (&f)[8])
     f[6] = __uint_as_float(raw.w << 16); f[7] = __uint_as_float(raw.w & 0xffff0000u);
 }
 
-__device__ __forceinline__ void unpack(const uint4 &raw, float (&f)[4])
+__device__ __forceinline__ void unpack(const u32x4 &raw, float (&f)[4])
 {
     f[0] = __uint_as_float(raw.x); f[1] = __uint_as_float(raw.y);
     f[2] = __uint_as_float(raw.z); f[3] = __uint_as_float(raw.w);
 }
 
-__device__ __forceinline__ uint4 load16(const char *p)
+// The caches are read exactly once per call: non-temporal loads keep them from displacing the small,
+// re-read score and statistics buffers in L2 (and measure ~10% faster than plain loads on a pure stream).
+__device__ __forceinline__ u32x4 stream16(const char *p)
 {
-    return *reinterpret_cast<const uint4 *>(p);
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(p));
 }
 
 // x + (x of the lane selected by a DPP control) -- cross-lane adds inside a 16-lane DPP row
@@ -78,7 +87,7 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
-// Workgroup-wide reductions over 4 waves; `red` is 4 floats of LDS, reusable right after return.
+// Workgroup-wide reductions over the waves; `red` is kWaves floats of LDS, reusable right after return.
 __device__ __forceinline__ float block_max(float x, float *red)
 {
     x = wave_max(x);
@@ -99,26 +108,30 @@ __device__ __forceinline__ float block_sum(float x, float *red)
     return x;
 }
 
+// Row (relative to the start of the chunk) that lane group `rg` of wave `w` reads with load `u` of its
+// `it`-th batch: batches of BATCH consecutive rows are dealt to the waves round-robin.
+template <bool BF16>
+__device__ __forceinline__ int batch_row(int it, int w, int u, int rg)
+{
+    return (it * kWaves + w) * Tile<BF16>::BATCH + u * Tile<BF16>::RPW + rg;
+}
+
 // ---------------------------------------------------------------------------------------------------------
-// Score kernel: s[b][j][t] = scale * q[b][rep(b,j)] . Kc[b][j][t], plus (max, sum of exp) per chunk.
-// grid = (n_cs, k, B).  Also clears the split counters the value kernel uses.
+// Score kernel: s[b][j][t] = scale * q[b][rep(b,j)] . Kc[b][j][t], plus (max, sum of exp) per chunk of cs
+// tokens.  grid = (n_cs, k, B).
 // ---------------------------------------------------------------------------------------------------------
 template <bool BF16, bool IDENT>
 __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ q, const char *__restrict__ kc,
                                                        const int32_t *__restrict__ rep, int H, int k, int T,
                                                        int Tc_cap, float scale, int cs, int n_cs,
-                                                       float *__restrict__ scores, float2 *__restrict__ stats,
-                                                       unsigned int *__restrict__ counters)
+                                                       float *__restrict__ scores, float2 *__restrict__ stats)
 {
     using TL = Tile<BF16>;
     __shared__ float s_lds[kMaxCs];
-    __shared__ float red[4];
+    __shared__ float red[kWaves];
 
     const int tid = threadIdx.x;
     const int chunk = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
-
-    if (chunk == 0 && j == 0)
-        for (int i = tid; i < H; i += kBlock) counters[(size_t)b * H + i] = 0u;
 
     int r = IDENT ? j : rep[(size_t)b * k + j];
     if (r < 0) return;                       // unused cluster slot (same decision for the whole workgroup)
@@ -129,28 +142,42 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
     const int t0 = chunk * cs;
     const int n = min(T, t0 + cs) - t0;      // >= 1 by construction of n_cs
 
-    float qf[TL::EPL];
-    unpack(load16(q + ((size_t)b * H + r) * TL::ROW_BYTES + cg * 16), qf);
-
     const char *kbase = kc + (((size_t)b * k + j) * Tc_cap + t0) * TL::ROW_BYTES + cg * 16;
-    const int n_iter = (n + TL::RPB - 1) / TL::RPB;
-    for (int i0 = 0; i0 < n_iter; i0 += kUnroll) {
-        uint4 raw[kUnroll];
+    const int n_it = (n + TL::BATCH * kWaves - 1) / (TL::BATCH * kWaves);
+
+    // every load of the chunk is issued before the first one is used (cs <= 256: at most 2 batches per wave
+    // in bf16, 4 in fp32)
+    constexpr int kMaxIt = kMaxCs / (TL::BATCH * kWaves);
+    u32x4 raw[kMaxIt][kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int tl = (i0 + u) * TL::RPB + w * TL::RPW + rg;
-            raw[u] = load16(kbase + (size_t)min(tl, n - 1) * TL::ROW_BYTES);
+    for (int it = 0; it < kMaxIt; ++it) {
+        if (it < n_it) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                raw[it][u] = stream16(kbase + (size_t)min(batch_row<BF16>(it, w, u, rg), n - 1) * TL::ROW_BYTES);
         }
+    }
+
+    float qf[TL::EPL];
+    {
+        const u32x4 qraw = *reinterpret_cast<const u32x4 *>(q + ((size_t)b * H + r) * TL::ROW_BYTES + cg * 16);
+        unpack(qraw, qf);
+    }
+
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int tl = (i0 + u) * TL::RPB + w * TL::RPW + rg;
-            float f[TL::EPL];
-            unpack(raw[u], f);
-            float dot = 0.f;
+    for (int it = 0; it < kMaxIt; ++it) {
+        if (it < n_it) {
 #pragma unroll
-            for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
-            dot = row_sum<BF16>(dot);
-            if (cg == 0 && tl < n) s_lds[tl] = scale * dot;
+            for (int u = 0; u < kUnroll; ++u) {
+                const int tl = batch_row<BF16>(it, w, u, rg);
+                float f[TL::EPL];
+                unpack(raw[it][u], f);
+                float dot = 0.f;
+#pragma unroll
+                for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
+                dot = row_sum<BF16>(dot);
+                if (cg == 0 && tl < n) s_lds[tl] = scale * dot;
+            }
         }
     }
     __syncthreads();
@@ -165,77 +192,107 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
 
 // ---------------------------------------------------------------------------------------------------------
 // Value kernel: out[b][h] = sum_t p_c[t] * V[b][h][t], c = cluster of h.  grid = (n_cp, H, B).
-// Each workgroup merges the chunk statistics of its cluster into the global (max, denominator), turns its
-// chunk of scores into final probabilities in LDS, streams its chunk of V, and writes a partial output; the
-// workgroup that finishes last for a head adds the partials in chunk order.
+//
+// Every wave works on its own: it merges the chunk statistics of its cluster into the row maximum M and the
+// denominator (exact merge of the chunks), and then, batch by batch, its first BATCH lanes turn one score
+// each into a final probability exp(s - M) / denominator, hand them to the other lanes through a private
+// LDS strip, and all lanes accumulate p * V for the rows they loaded.  The loads of the next batch (V rows
+// and scores) are issued before the current batch is consumed, and the first batch is requested before the
+// statistics are merged, so the stream never drains; the only workgroup barrier is the one that adds up the
+// four waves at the end.  With one chunk per head the sum goes to `out`, otherwise to a partial row that
+// combine_kernel adds up in chunk order.
 // ---------------------------------------------------------------------------------------------------------
 template <bool BF16, bool IDENT>
 __global__ __launch_bounds__(kBlock) void value_kernel(const char *__restrict__ v, const int32_t *__restrict__ h2c,
                                                        const int32_t *__restrict__ rep, int H, int k, int T,
                                                        int T_cap, int n_cs, int cp, int n_cp,
                                                        const float *__restrict__ scores,
-                                                       const float2 *__restrict__ stats, float *partial,
-                                                       unsigned int *counters, float *__restrict__ out,
+                                                       const float2 *__restrict__ stats,
+                                                       float *__restrict__ partial, float *__restrict__ out,
                                                        float *__restrict__ probs_out)
 {
     using TL = Tile<BF16>;
-    __shared__ float p_lds[kMaxCp];
-    __shared__ float red[4];
-    __shared__ float acc_lds[kBlock / 64][kHeadDim];
-    __shared__ int last_flag;
+    __shared__ float p_lds[kWaves][TL::BATCH];
+    __shared__ float acc_lds[kWaves][kHeadDim];
 
     const int tid = threadIdx.x;
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int c = IDENT ? h : min(max(h2c[(size_t)b * H + h], 0), k - 1);
-    const size_t crow = (size_t)b * k + c;
-    const int t0 = split * cp;
-    const int n = min(T, t0 + cp) - t0;
-
-    // softmax statistics of the whole row from the per-chunk records (exact merge of the chunks)
-    const float2 *st = stats + crow * n_cs;
-    float m = -INFINITY;
-    for (int i = tid; i < n_cs; i += kBlock) m = fmaxf(m, st[i].x);
-    const float M = block_max(m, red);
-    float l = 0.f;
-    for (int i = tid; i < n_cs; i += kBlock) l += st[i].y * expf(st[i].x - M);
-    const float inv = 1.0f / block_sum(l, red);
-
-    const bool write_p = probs_out != nullptr && (IDENT || rep[crow] == h);
-    for (int i = tid; i < n; i += kBlock) {
-        const float p = expf(scores[crow * T + t0 + i] - M) * inv;
-        p_lds[i] = p;
-        if (write_p) probs_out[crow * T + t0 + i] = p;
-    }
-    __syncthreads();
-
     const int lane = tid & 63, w = tid >> 6;
     const int cg = lane % TL::LPR, rg = lane / TL::LPR;
+    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int t0 = split * cp;
+    const int n = min(T, t0 + cp) - t0;
+    const int n_batches = (n + TL::BATCH - 1) / TL::BATCH;
+    const int n_it = n_batches > w ? (n_batches - w + kWaves - 1) / kWaves : 0;     // batches of this wave
+
     const char *vbase = v + (((size_t)b * H + h) * T_cap + t0) * TL::ROW_BYTES + cg * 16;
+
+    u32x4 cur[kUnroll];
+    if (n_it > 0) {
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            cur[u] = stream16(vbase + (size_t)min(batch_row<BF16>(0, w, u, rg), n - 1) * TL::ROW_BYTES);
+    }
+
+    const int c = IDENT ? h : min(max(h2c[(size_t)b * H + h], 0), k - 1);
+    const size_t crow = (size_t)b * k + c;
+    const float *srow = scores + crow * T + t0;
+    float *prow = (probs_out != nullptr && (IDENT || rep[crow] == h)) ? probs_out + crow * T + t0 : nullptr;
+
+    // the score this lane turns into a probability for batch `it` (lanes >= BATCH and rows past the end: none)
+    auto score_of = [&](int it) -> float {
+        const int tl = (it * kWaves + w) * TL::BATCH + lane;
+        return (lane < TL::BATCH && tl < n) ? srow[tl] : -INFINITY;
+    };
+    float s_cur = n_it > 0 ? score_of(0) : -INFINITY;
+
+    const float2 *st = stats + crow * n_cs;
+    float m = -INFINITY;
+    for (int i = lane; i < n_cs; i += 64) m = fmaxf(m, st[i].x);
+    const float M = wave_max(m);
+    float l = 0.f;
+    for (int i = lane; i < n_cs; i += 64) l += st[i].y * expf(st[i].x - M);
+    const float inv = 1.0f / wave_sum(l);
 
     float acc[TL::EPL];
 #pragma unroll
     for (int e = 0; e < TL::EPL; ++e) acc[e] = 0.f;
 
-    const int n_iter = (n + TL::RPB - 1) / TL::RPB;
-    for (int i0 = 0; i0 < n_iter; i0 += kUnroll) {
-        uint4 raw[kUnroll];
+    for (int it = 0; it < n_it; ++it) {
+        // requests of the next batch
+        u32x4 nxt[kUnroll];
+        float s_nxt = -INFINITY;
+        if (it + 1 < n_it) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u)
+                nxt[u] = stream16(vbase + (size_t)min(batch_row<BF16>(it + 1, w, u, rg), n - 1) * TL::ROW_BYTES);
+            s_nxt = score_of(it + 1);
+        }
+        // probabilities of this batch: lane i < BATCH owns row i of the batch; slot rg*kUnroll + u holds the
+        // row that lane group rg multiplies with its load u, so a lane reads kUnroll consecutive floats
+        const float p = expf(s_cur - M) * inv;          // exp(-inf) = 0 for rows past the end
+        if (lane < TL::BATCH) {
+            p_lds[w][(lane % TL::RPW) * kUnroll + lane / TL::RPW] = p;
+            const int tl = (it * kWaves + w) * TL::BATCH + lane;
+            if (prow != nullptr && tl < n) prow[tl] = p;
+        }
+        __builtin_amdgcn_wave_barrier();
         float pv[kUnroll];
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const int tl = (i0 + u) * TL::RPB + w * TL::RPW + rg;
-            raw[u] = load16(vbase + (size_t)min(tl, n - 1) * TL::ROW_BYTES);
-            pv[u] = tl < n ? p_lds[tl] : 0.f;
-        }
+        for (int u = 0; u < kUnroll; ++u) pv[u] = p_lds[w][rg * kUnroll + u];
+        __builtin_amdgcn_wave_barrier();
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             float f[TL::EPL];
-            unpack(raw[u], f);
+            unpack(cur[u], f);
 #pragma unroll
             for (int e = 0; e < TL::EPL; ++e) acc[e] = fmaf(pv[u], f[e], acc[e]);
         }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) cur[u] = nxt[u];
+        s_cur = s_nxt;
     }
 
-    // rows of one wave load, then the four waves
+    // lane groups of a wave, then the waves
 #pragma unroll
     for (int e = 0; e < TL::EPL; ++e) {
         if (BF16) acc[e] += __shfl_xor(acc[e], 16);
@@ -246,43 +303,34 @@ __global__ __launch_bounds__(kBlock) void value_kernel(const char *__restrict__ 
         for (int e = 0; e < TL::EPL; ++e) acc_lds[w][cg * TL::EPL + e] = acc[e];
     }
     __syncthreads();
-    float val = 0.f;
-    if (tid < kHeadDim) val = (acc_lds[0][tid] + acc_lds[1][tid]) + (acc_lds[2][tid] + acc_lds[3][tid]);
-
-    const size_t orow = (size_t)b * H + h;
-    if (n_cp == 1) {
-        if (tid < kHeadDim) out[orow * kHeadDim + tid] = val;
-        return;
-    }
-
-    if (tid < kHeadDim) partial[(orow * n_cp + split) * kHeadDim + tid] = val;
-    __threadfence();                                   // partials visible device-wide before the count
-    __syncthreads();
-    if (tid == 0) last_flag = (atomicAdd(&counters[orow], 1u) == (unsigned int)(n_cp - 1));
-    __syncthreads();
-    if (!last_flag) return;
-    __threadfence();                                   // see the other workgroups' partials
     if (tid < kHeadDim) {
-        float sum = 0.f;
-        for (int s = 0; s < n_cp; ++s)
-            sum += __hip_atomic_load(&partial[(orow * n_cp + s) * kHeadDim + tid], __ATOMIC_RELAXED,
-                                     __HIP_MEMORY_SCOPE_AGENT);
-        out[orow * kHeadDim + tid] = sum;
+        const float val = (acc_lds[0][tid] + acc_lds[1][tid]) + (acc_lds[2][tid] + acc_lds[3][tid]);
+        const size_t orow = (size_t)b * H + h;
+        if (n_cp == 1) out[orow * kHeadDim + tid] = val;
+        else partial[(orow * n_cp + split) * kHeadDim + tid] = val;
     }
+}
+
+// Sum of the partial rows of every head in chunk order.  grid = (B*H), 128 threads.
+__global__ __launch_bounds__(kHeadDim) void combine_kernel(const float *__restrict__ partial, int n_cp,
+                                                           float *__restrict__ out)
+{
+    const size_t orow = blockIdx.x;
+    float sum = 0.f;
+    for (int s = 0; s < n_cp; ++s) sum += partial[(orow * n_cp + s) * kHeadDim + threadIdx.x];
+    out[orow * kHeadDim + threadIdx.x] = sum;
 }
 
 struct Workspace {
     float *scores;
     float2 *stats;
     float *partial;
-    unsigned int *counters;
     Workspace(void *base, const DecodePlan &pl)
     {
         char *ws = static_cast<char *>(base);
         scores = reinterpret_cast<float *>(ws + pl.off_scores);
         stats = reinterpret_cast<float2 *>(ws + pl.off_stats);
         partial = reinterpret_cast<float *>(ws + pl.off_partial);
-        counters = reinterpret_cast<unsigned int *>(ws + pl.off_counter);
     }
 };
 
@@ -292,7 +340,7 @@ int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H
 {
     score_kernel<BF16, IDENT><<<dim3(pl.n_cs, k, B), kBlock, 0, stream>>>(
         static_cast<const char *>(q), static_cast<const char *>(kc), rep, H, k, T, Tc_cap, scale, pl.cs, pl.n_cs,
-        w.scores, w.stats, w.counters);
+        w.scores, w.stats);
     return (int)hipGetLastError();
 }
 
@@ -301,8 +349,11 @@ int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, i
                  float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, hipStream_t stream)
 {
     value_kernel<BF16, IDENT><<<dim3(pl.n_cp, H, B), kBlock, 0, stream>>>(
-        static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs, pl.cp, pl.n_cp, w.scores, w.stats,
-        w.partial, w.counters, out, probs_out);
+        static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs, pl.cp, pl.n_cp, w.scores, w.stats, w.partial,
+        out, probs_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.n_cp == 1) return (int)e;
+    combine_kernel<<<dim3(B * H), kHeadDim, 0, stream>>>(w.partial, pl.n_cp, out);
     return (int)hipGetLastError();
 }
 
@@ -318,12 +369,21 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
     for (int c : {256, 128}) {
         if ((long long)B * k * ((T + c - 1) / c) >= 1024) { pl.cs = c; break; }
     }
-    pl.n_cs = (T + pl.cs - 1) / pl.cs;
-    // value chunk: the largest of 1024/512/256 tokens that still gives >= 2048 workgroups (8 per CU)
-    pl.cp = 128;
-    for (int c : {1024, 512, 256}) {
-        if ((long long)B * H * ((T + c - 1) / c) >= 2048) { pl.cp = c; break; }
+    // value chunk: whole rows of the cache per workgroup while that gives >= 512 workgroups (2 per CU, all
+    // resident at once, no partial rows); otherwise the fewest chunks of >= 128 tokens that reach 512
+    {
+        const long long heads = (long long)B * H > 0 ? (long long)B * H : 1;
+        long long want = heads >= 512 ? 1 : (512 + heads - 1) / heads;
+        const long long most = (T + 127) / 128;
+        if (want > most) want = most;
+        pl.cp = (int)(((T + want - 1) / want + 127) / 128 * 128);
     }
+#ifdef CHAI_TUNING
+    // experiment hooks, compiled only into tuning builds
+    if (const char *e = getenv("CHAI_CS")) pl.cs = atoi(e);
+    if (const char *e = getenv("CHAI_CP")) pl.cp = atoi(e);
+#endif
+    pl.n_cs = (T + pl.cs - 1) / pl.cs;
     pl.n_cp = (T + pl.cp - 1) / pl.cp;
 
     // Region sizes are upper bounds over every chunking the rules above can pick (smallest chunks), so the
@@ -333,7 +393,6 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
     pl.off_scores = off;  off = align_up(off + (size_t)B * k * T * sizeof(float), 256);
     pl.off_stats = off;   off = align_up(off + (size_t)B * k * max_n_cs * sizeof(float2), 256);
     pl.off_partial = off; off = align_up(off + (size_t)B * H * max_n_cp * kHeadDim * sizeof(float), 256);
-    pl.off_counter = off; off = align_up(off + (size_t)B * H * sizeof(unsigned int), 256);
     pl.bytes = off;
     return pl;
 }

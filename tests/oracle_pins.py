@@ -102,14 +102,14 @@ def pin_dense_matches_library():
                 k[:, :, T:], v[:, :, T:] = np.nan, np.nan
             else:
                 k[:, :, T:], v[:, :, T:] = 0x7FC0, 0x7FC0
-        scale = 1.0 / math.sqrt(d)
+        scale = float(np.float32(1.0 / math.sqrt(d)))
         out, p = O.dense_decode(q, k, v, T, scale, want_probs=True)
         ref, pref = lib_dense(q, k, v, T, scale)
         assert np.allclose(p, pref, rtol=1e-12, atol=1e-15)
         assert np.allclose(out, ref, rtol=1e-12, atol=1e-13)
         # the scale really multiplies the scores
-        out2 = O.dense_decode(q, k, v, T, 0.37)
-        assert np.allclose(out2, lib_dense(q, k, v, T, 0.37)[0], rtol=1e-12, atol=1e-13)
+        out2 = O.dense_decode(q, k, v, T, 0.375)
+        assert np.allclose(out2, lib_dense(q, k, v, T, 0.375)[0], rtol=1e-12, atol=1e-13)
 
 
 def pin_dense_closed_forms():
@@ -135,7 +135,7 @@ def pin_dense_closed_forms():
 
 def pin_softmax_properties():
     q, k, v = _rand_case(11, 2, 4, 50, 50, 32, W.F32)
-    scale = 1.0 / math.sqrt(32)
+    scale = float(np.float32(1.0 / math.sqrt(32)))
     _, p = O.dense_decode(q, k, v, 50, scale, want_probs=True)
     assert np.all(p >= 0) and np.allclose(p.sum(-1), 1.0, rtol=0, atol=1e-14)
     # adding one vector u to every key shifts all scores of a head by the same constant
@@ -154,7 +154,7 @@ def pin_clustered_reduces_to_dense():
     for seed, dt in [(21, W.F32), (22, W.BF16)]:
         B, H, T, T_cap, d = 2, 6, 23, 29, 64
         q, k, v = _rand_case(seed, B, H, T, T_cap, d, dt)
-        scale = 1.0 / math.sqrt(d)
+        scale = float(np.float32(1.0 / math.sqrt(d)))
         dense = O.dense_decode(q, k, v, T, scale)
         # one head per cluster (any labelling) is dense attention
         g = np.random.default_rng(seed)
@@ -171,7 +171,7 @@ def pin_clustered_matches_library():
         B, H, T, T_cap, d, kk = 2, 7, 19, 19, 32, 3
         q, k, v = _rand_case(seed, B, H, T, T_cap, d, dt)
         h2c, rep = W.random_membership(np.random.default_rng(seed), B, H, kk)
-        scale = 1.0 / math.sqrt(d)
+        scale = float(np.float32(1.0 / math.sqrt(d)))
         out, p = O.clustered_decode(q, k, v, h2c, rep, T, scale, want_probs=True)
         ref = lib_clustered(q, k, v, h2c, rep, T, scale)
         assert np.allclose(out, ref, rtol=1e-12, atol=1e-13)
@@ -192,7 +192,7 @@ def pin_clustered_identical_qk_is_exact():
     q = np.stack([qc[b, h2c[b]] for b in range(B)])
     k = np.stack([kc[b, h2c[b]] for b in range(B)])
     v = W.normal(g, (B, H, T, d), W.F32)
-    scale = 1.0 / math.sqrt(d)
+    scale = float(np.float32(1.0 / math.sqrt(d)))
     dense = O.dense_decode(q, k, v, T, scale)
     out, p = O.clustered_decode(q, k, v, h2c, rep, T, scale, want_probs=True)
     assert np.array_equal(out, dense)
@@ -249,7 +249,7 @@ def pin_features_match_library():
         g = np.random.default_rng(seed)
         q5 = W.normal(g, (B, H, n, d), dt)
         kc = W.normal(g, (B, H, 11, d), dt)          # keys read in place from a longer cache
-        scale = 1.0 / math.sqrt(d)
+        scale = float(np.float32(1.0 / math.sqrt(d)))
         feat = O.score_features(q5, kc, scale, n_tok=n)
         s = scale * np.einsum("bhid,bhjd->bhij", W.as_f64(q5), W.as_f64(kc)[:, :, :n])
         s = np.where(np.tril(np.ones((n, n), bool)), s, -np.inf)

@@ -155,10 +155,9 @@ def random_membership(g: np.random.Generator, B: int, H: int, k: int) -> Tuple[n
     """Uniformly random head->cluster maps with every cluster non-empty; representative = lowest member."""
     h2c = np.empty((B, H), np.int32)
     for b in range(B):
-        while True:
-            a = g.integers(0, k, size=H)
-            if len(np.unique(a)) == k:
-                break
+        # k randomly chosen heads seed the k clusters (so none is empty), the others fall uniformly
+        a = g.integers(0, k, size=H)
+        a[g.choice(H, size=k, replace=False)] = np.arange(k)
         h2c[b] = a
     return h2c, representatives(h2c, k)
 
