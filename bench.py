@@ -106,30 +106,62 @@ def timed_steps(fn, steps, warmup, torch):
     return e0.elapsed_time(e1) / steps, wall
 
 
+class HipEvents:
+    """hipEvent_t handles from the HIP runtime that is already loaded in this process (torch's), so that the
+    library can have the runtime stamp the begin and the end of a kernel into them."""
+
+    def __init__(self):
+        import ctypes
+        paths = sorted({l.split()[-1] for l in open("/proc/self/maps") if "libamdhip64" in l})
+        if not paths:
+            raise RuntimeError("no HIP runtime loaded")
+        self.ct = ctypes
+        self.hip = ctypes.CDLL(paths[0])
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+        self.made = []
+
+    def create(self) -> int:
+        ev = self.ct.c_void_p()
+        rc = self.hip.hipEventCreate(self.ct.byref(ev))
+        if rc != 0:
+            raise RuntimeError(f"hipEventCreate failed ({rc})")
+        self.made.append(ev.value)
+        return ev.value
+
+    def elapsed_ms(self, a: int, b: int) -> float:
+        ms = self.ct.c_float()
+        rc = self.hip.hipEventElapsedTime(self.ct.byref(ms), a, b)
+        if rc != 0:
+            raise RuntimeError(f"hipEventElapsedTime failed ({rc})")
+        return float(ms.value)
+
+    def close(self):
+        for ev in self.made:
+            self.hip.hipEventDestroy(ev)
+        self.made = []
+
+
 def phase_timing(layers, cfg, ws, C, torch, steps):
-    """Average duration of the score kernel and of the value kernel per launch, from HIP events recorded on the
-    launch stream around each phase call (a separate pass, so the events do not perturb the headline timing)."""
-    n = len(layers) * steps
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(n)]
-    i = 0
-    for _ in range(steps):
-        for L in layers:
-            a, b, c = ev[i]
-            i += 1
-            a.record()
-            C.chai_decode_scores(L.q, L.kc, L.rep, cfg.T, cfg.scale, ws)
-            b.record()
-            C.chai_decode_values(L.v, L.h2c, L.rep, cfg.T, L.out, ws)
-            c.record()
-    torch.cuda.synchronize()
-    per_layer = {}
-    i = 0
+    """Average duration of the score kernel and of the value kernel per launch over `steps` more steps of the same
+    workload.  Each launch carries a pair of HIP events that the runtime stamps with the kernel's own begin and end
+    on the launch stream (so launch gaps are not counted, as in a profiler's kernel trace); a separate pass, so
+    the events do not perturb the headline timing."""
+    hev = HipEvents()
+    recs = []
     for _ in range(steps):
         for li, L in enumerate(layers):
-            a, b, c = ev[i]
-            i += 1
-            s, v = per_layer.setdefault(li, [0.0, 0.0])
-            per_layer[li] = [s + a.elapsed_time(b), v + b.elapsed_time(c)]
+            e = [hev.create() for _ in range(4)]
+            C.chai_decode_scores_timed(L.q, L.kc, L.rep, cfg.T, cfg.scale, ws, start_event=e[0], stop_event=e[1])
+            C.chai_decode_values_timed(L.v, L.h2c, L.rep, cfg.T, L.out, ws, start_event=e[2], stop_event=e[3])
+            recs.append((li, e))
+    torch.cuda.synchronize()
+    per_layer = {}
+    for li, e in recs:
+        s, v = per_layer.get(li, (0.0, 0.0))
+        per_layer[li] = (s + hev.elapsed_ms(e[0], e[1]), v + hev.elapsed_ms(e[2], e[3]))
+    hev.close()
     return {li: (s / steps, v / steps) for li, (s, v) in per_layer.items()}
 
 

@@ -204,6 +204,23 @@ int chai_decode_values(const void *v_cache, const int32_t *head_to_cluster, cons
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * For callers that profile the two kernels: the same calls with two more
+ * arguments, hipEvent_t handles passed as void* that the caller created with
+ * timing enabled (either may be NULL).  The runtime stamps start_event when
+ * the phase's kernel begins executing and stop_event when it has finished, so
+ * hipEventElapsedTime(start, stop) is the duration of the kernel itself,
+ * without launch gaps.  (When the value phase runs a combine kernel after the
+ * value kernel, the events cover the value kernel only.)
+ */
+int chai_decode_scores_timed(const void *q, const void *k_compact, const int32_t *rep_heads, int B, int H,
+                             int k, int T, int Tc_cap, int d, int dtype, float scale, void *workspace,
+                             size_t workspace_bytes, void *stream, void *start_event, void *stop_event);
+int chai_decode_values_timed(const void *v_cache, const int32_t *head_to_cluster, const int32_t *rep_heads,
+                             int B, int H, int k, int T, int T_cap, int d, int dtype, float *out,
+                             float *probs_out, void *workspace, size_t workspace_bytes, void *stream,
+                             void *start_event, void *stop_event);
+
+/*
  * Dense multi-head decode attention, the definition of Section 2
  * (A_h = softmax(q_h K_h^T / sqrt(d)), y = A_0 V_0 (+) A_1 V_1 ...): the
  * baseline clustered attention is compared against.  Runs the same kernels

@@ -23,7 +23,8 @@ STATUS_NAMES = {0: "CHAI_OK", 1: "CHAI_ERR_NULL", 2: "CHAI_ERR_SHAPE", 3: "CHAI_
 
 EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_assign_clusters",
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention",
-           "chai_decode_scores", "chai_decode_values", "chai_dense_decode_attention"]
+           "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
+           "chai_dense_decode_attention"]
 
 
 class ChaiError(RuntimeError):
@@ -52,6 +53,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_dense_decode_attention.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     L.chai_decode_scores.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
     L.chai_decode_values.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
+    L.chai_decode_scores_timed.argtypes = L.chai_decode_scores.argtypes + [vp, vp]
+    L.chai_decode_values_timed.argtypes = L.chai_decode_values.argtypes + [vp, vp]
     for fn in EXPORTS:
         if fn not in ("chai_status_string", "chai_decode_workspace_bytes"):
             getattr(L, fn).restype = ci
@@ -168,8 +171,33 @@ def chai_decode_attention(q, k_compact, v_cache, head_to_cluster, rep_heads, T: 
     return out
 
 
+def chai_decode_scores_timed(q, k_compact, rep_heads, T: int, scale: float, workspace, stream=None, start_event=None,
+                             stop_event=None):
+    """First phase of chai_decode_attention: scores and chunk statistics of every cluster into the workspace.
+    start_event / stop_event: raw hipEvent_t handles (ints) stamped with the kernel's begin and end, or None."""
+    B, H, d = q.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    _check("chai_decode_scores_timed",
+           _lib.chai_decode_scores_timed(_ptr(q), _ptr(k_compact), _ptr(rep_heads), B, H, k, T, Tc_cap, d,
+                                         dtype_code(q), scale, _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream), start_event,
+                                         stop_event))
+
+
+def chai_decode_values_timed(v_cache, head_to_cluster, rep_heads, T: int, out, workspace, probs_out=None, stream=None,
+                             start_event=None, stop_event=None):
+    """Second phase of chai_decode_attention: probabilities from the workspace applied to every head's values."""
+    B, H, T_cap, d = v_cache.shape
+    k = rep_heads.shape[1]
+    _check("chai_decode_values_timed",
+           _lib.chai_decode_values_timed(_ptr(v_cache), _ptr(head_to_cluster), _ptr(rep_heads), B, H, k, T, T_cap, d,
+                                         dtype_code(v_cache), _ptr(out), _ptr(probs_out), _ptr(workspace),
+                                         workspace.numel() * workspace.element_size(), _stream(stream), start_event,
+                                         stop_event))
+    return out
+
+
 def chai_decode_scores(q, k_compact, rep_heads, T: int, scale: float, workspace, stream=None):
-    """First phase of chai_decode_attention: scores and chunk statistics of every cluster into the workspace."""
     B, H, d = q.shape
     k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
     _check("chai_decode_scores",
@@ -179,7 +207,6 @@ def chai_decode_scores(q, k_compact, rep_heads, T: int, scale: float, workspace,
 
 
 def chai_decode_values(v_cache, head_to_cluster, rep_heads, T: int, out, workspace, probs_out=None, stream=None):
-    """Second phase of chai_decode_attention: probabilities from the workspace applied to every head's values."""
     B, H, T_cap, d = v_cache.shape
     k = rep_heads.shape[1]
     _check("chai_decode_values",

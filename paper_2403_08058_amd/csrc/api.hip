@@ -128,30 +128,53 @@ size_t chai_decode_workspace_bytes(int B, int H, int k, int T, int d, int dtype)
     return make_decode_plan(B, H, k, T).bytes;
 }
 
-int chai_decode_scores(const void *q, const void *k_compact, const int32_t *rep_heads, int B, int H, int k, int T,
-                       int Tc_cap, int d, int dtype, float scale, void *workspace, size_t workspace_bytes,
-                       void *stream)
+int chai_decode_scores_timed(const void *q, const void *k_compact, const int32_t *rep_heads, int B, int H, int k,
+                             int T, int Tc_cap, int d, int dtype, float scale, void *workspace,
+                             size_t workspace_bytes, void *stream, void *start_event, void *stop_event)
 {
     if (!rep_heads) return CHAI_ERR_NULL;
     DecodePlan plan;
     const int st = check_scores(q, k_compact, B, H, k, T, Tc_cap, d, dtype, workspace, workspace_bytes, &plan);
     if (st != CHAI_OK) return st;
     if (B == 0) return CHAI_OK;
+    KernelEvents ev;
+    ev.start = static_cast<hipEvent_t>(start_event);
+    ev.stop = static_cast<hipEvent_t>(stop_event);
     return hip_status(launch_scores(q, k_compact, rep_heads, B, H, k, T, Tc_cap, dtype, scale, workspace, plan, false,
-                                    static_cast<hipStream_t>(stream)));
+                                    ev, static_cast<hipStream_t>(stream)));
 }
 
-int chai_decode_values(const void *v_cache, const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H,
-                       int k, int T, int T_cap, int d, int dtype, float *out, float *probs_out, void *workspace,
-                       size_t workspace_bytes, void *stream)
+int chai_decode_values_timed(const void *v_cache, const int32_t *head_to_cluster, const int32_t *rep_heads, int B,
+                             int H, int k, int T, int T_cap, int d, int dtype, float *out, float *probs_out,
+                             void *workspace, size_t workspace_bytes, void *stream, void *start_event,
+                             void *stop_event)
 {
     if (!head_to_cluster || !rep_heads) return CHAI_ERR_NULL;
     DecodePlan plan;
     const int st = check_values(v_cache, out, B, H, k, T, T_cap, d, dtype, workspace, workspace_bytes, &plan);
     if (st != CHAI_OK) return st;
     if (B == 0) return CHAI_OK;
+    KernelEvents ev;
+    ev.start = static_cast<hipEvent_t>(start_event);
+    ev.stop = static_cast<hipEvent_t>(stop_event);
     return hip_status(launch_values(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, dtype, out, probs_out,
-                                    workspace, plan, false, static_cast<hipStream_t>(stream)));
+                                    workspace, plan, false, ev, static_cast<hipStream_t>(stream)));
+}
+
+int chai_decode_scores(const void *q, const void *k_compact, const int32_t *rep_heads, int B, int H, int k, int T,
+                       int Tc_cap, int d, int dtype, float scale, void *workspace, size_t workspace_bytes,
+                       void *stream)
+{
+    return chai_decode_scores_timed(q, k_compact, rep_heads, B, H, k, T, Tc_cap, d, dtype, scale, workspace,
+                                    workspace_bytes, stream, nullptr, nullptr);
+}
+
+int chai_decode_values(const void *v_cache, const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H,
+                       int k, int T, int T_cap, int d, int dtype, float *out, float *probs_out, void *workspace,
+                       size_t workspace_bytes, void *stream)
+{
+    return chai_decode_values_timed(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, d, dtype, out, probs_out,
+                                    workspace, workspace_bytes, stream, nullptr, nullptr);
 }
 
 int chai_decode_attention(const void *q, const void *k_compact, const void *v_cache, const int32_t *head_to_cluster,
@@ -166,10 +189,11 @@ int chai_decode_attention(const void *q, const void *k_compact, const void *v_ca
     if (st != CHAI_OK) return st;
     if (B == 0) return CHAI_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = hip_status(launch_scores(q, k_compact, rep_heads, B, H, k, T, Tc_cap, dtype, scale, workspace, plan, false, s));
+    st = hip_status(launch_scores(q, k_compact, rep_heads, B, H, k, T, Tc_cap, dtype, scale, workspace, plan, false,
+                                  KernelEvents(), s));
     if (st != CHAI_OK) return st;
     return hip_status(launch_values(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, dtype, out, probs_out,
-                                    workspace, plan, false, s));
+                                    workspace, plan, false, KernelEvents(), s));
 }
 
 int chai_dense_decode_attention(const void *q, const void *k_cache, const void *v_cache, int B, int H, int T,
@@ -182,10 +206,11 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
     if (st != CHAI_OK) return st;
     if (B == 0) return CHAI_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    st = hip_status(launch_scores(q, k_cache, nullptr, B, H, H, T, T_cap, dtype, scale, workspace, plan, true, s));
+    st = hip_status(launch_scores(q, k_cache, nullptr, B, H, H, T, T_cap, dtype, scale, workspace, plan, true,
+                                  KernelEvents(), s));
     if (st != CHAI_OK) return st;
     return hip_status(launch_values(v_cache, nullptr, nullptr, B, H, H, T, T_cap, dtype, out, nullptr, workspace, plan,
-                                    true, s));
+                                    true, KernelEvents(), s));
 }
 
 }  // extern "C"

@@ -24,14 +24,20 @@ struct DecodePlan {
 
 DecodePlan make_decode_plan(int B, int H, int k, int T);
 
+// Optional events the runtime stamps with the begin and the end of a kernel (NULL = not wanted).
+struct KernelEvents {
+    hipEvent_t start = nullptr;
+    hipEvent_t stop = nullptr;
+};
+
 // Enqueue the two kernels of one decode call.  identity = true: every head is its own cluster and the maps
 // are not read (dense attention).  Each returns a hipError_t as int.
 int launch_scores(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap,
                   int dtype, float scale, void *workspace, const DecodePlan &plan, bool identity,
-                  hipStream_t stream);
+                  const KernelEvents &ev, hipStream_t stream);
 int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
-                  hipStream_t stream);
+                  const KernelEvents &ev, hipStream_t stream);
 
 int launch_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int dtype, int64_t qs,
                           int64_t ks, float scale, float *feat, hipStream_t stream);

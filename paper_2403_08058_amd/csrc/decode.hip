@@ -8,6 +8,8 @@
 // query and keys, shared by the member heads, each applying it to its own values (Sections 3.4-3.5, Fig. 3).
 #include "chai_internal.h"
 
+#include <hip/hip_ext.h>
+
 #ifdef CHAI_TUNING
 #include <cstdlib>
 #endif
@@ -18,7 +20,9 @@ namespace {
 
 constexpr int kUnroll = 8;        // 16-byte loads per lane in one batch
 constexpr int kMaxCs = 256;       // largest score chunk (= workgroup size: one thread per score)
-constexpr int kWaves = kBlock / 64;
+constexpr int kWaves = kBlock / 64;   // waves per workgroup of the score kernel
+constexpr int kValueWaves = 4;    // waves per workgroup of the value kernel
+constexpr int kValueBatches = 2;  // batches each wave of the value kernel keeps in flight
 
 template <bool BF16>
 struct Tile {
@@ -133,9 +137,6 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
     const int tid = threadIdx.x;
     const int chunk = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
 
-    int r = IDENT ? j : rep[(size_t)b * k + j];
-    if (r < 0) return;                       // unused cluster slot (same decision for the whole workgroup)
-    r = min(r, H - 1);
 
     const int lane = tid & 63, w = tid >> 6;
     const int cg = lane % TL::LPR, rg = lane / TL::LPR;
@@ -145,8 +146,9 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
     const char *kbase = kc + (((size_t)b * k + j) * Tc_cap + t0) * TL::ROW_BYTES + cg * 16;
     const int n_it = (n + TL::BATCH * kWaves - 1) / (TL::BATCH * kWaves);
 
-    // every load of the chunk is issued before the first one is used (cs <= 256: at most 2 batches per wave
-    // in bf16, 4 in fp32)
+    // Every load of the chunk is issued before anything else (cs <= 256: at most 2 batches per wave in bf16, 4
+    // in fp32), including the lookup of the representative: the key stream of a cluster slot does not depend
+    // on who represents it, and an unused slot's keys are still readable memory.
     constexpr int kMaxIt = kMaxCs / (TL::BATCH * kWaves);
     u32x4 raw[kMaxIt][kUnroll];
 #pragma unroll
@@ -157,6 +159,10 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
                 raw[it][u] = stream16(kbase + (size_t)min(batch_row<BF16>(it, w, u, rg), n - 1) * TL::ROW_BYTES);
         }
     }
+
+    int r = IDENT ? j : rep[(size_t)b * k + j];
+    if (r < 0) return;                       // unused cluster slot (same decision for the whole workgroup)
+    r = min(r, H - 1);
 
     float qf[TL::EPL];
     {
@@ -202,18 +208,18 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
 // four waves at the end.  With one chunk per head the sum goes to `out`, otherwise to a partial row that
 // combine_kernel adds up in chunk order.
 // ---------------------------------------------------------------------------------------------------------
-template <bool BF16, bool IDENT>
-__global__ __launch_bounds__(kBlock) void value_kernel(const char *__restrict__ v, const int32_t *__restrict__ h2c,
-                                                       const int32_t *__restrict__ rep, int H, int k, int T,
-                                                       int T_cap, int n_cs, int cp, int n_cp,
-                                                       const float *__restrict__ scores,
-                                                       const float2 *__restrict__ stats,
-                                                       float *__restrict__ partial, float *__restrict__ out,
-                                                       float *__restrict__ probs_out)
+template <bool BF16, bool IDENT, int NW, int NB>
+__global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__ v, const int32_t *__restrict__ h2c,
+                                                        const int32_t *__restrict__ rep, int H, int k, int T,
+                                                        int T_cap, int n_cs, int cp, int n_cp,
+                                                        const float *__restrict__ scores,
+                                                        const float2 *__restrict__ stats,
+                                                        float *__restrict__ partial, float *__restrict__ out,
+                                                        float *__restrict__ probs_out)
 {
     using TL = Tile<BF16>;
-    __shared__ float p_lds[kWaves][TL::BATCH];
-    __shared__ float acc_lds[kWaves][kHeadDim];
+    __shared__ float p_lds[NW][TL::BATCH];
+    __shared__ float acc_lds[NW][kHeadDim];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
@@ -222,16 +228,28 @@ __global__ __launch_bounds__(kBlock) void value_kernel(const char *__restrict__ 
     const int t0 = split * cp;
     const int n = min(T, t0 + cp) - t0;
     const int n_batches = (n + TL::BATCH - 1) / TL::BATCH;
-    const int n_it = n_batches > w ? (n_batches - w + kWaves - 1) / kWaves : 0;     // batches of this wave
+    const int n_it = n_batches > w ? (n_batches - w + NW - 1) / NW : 0;     // batches of this wave
 
     const char *vbase = v + (((size_t)b * H + h) * T_cap + t0) * TL::ROW_BYTES + cg * 16;
 
-    u32x4 cur[kUnroll];
-    if (n_it > 0) {
+    // one batch: the 16-byte pieces of kUnroll * RPW consecutive rows, and (lanes < BATCH) one row's score
+    struct Batch {
+        u32x4 v[kUnroll];
+        float s;
+    };
+    Batch buf[NB];
+
+    // rows of batch `it` of this wave start at (it * NW + w) * BATCH within the chunk
+    auto request_v = [&](Batch &bt, int it) {
+        if (it < n_it) {
+            const int r0 = (it * NW + w) * TL::BATCH + rg;
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u)
-            cur[u] = stream16(vbase + (size_t)min(batch_row<BF16>(0, w, u, rg), n - 1) * TL::ROW_BYTES);
-    }
+            for (int u = 0; u < kUnroll; ++u)
+                bt.v[u] = stream16(vbase + (size_t)min(r0 + u * TL::RPW, n - 1) * TL::ROW_BYTES);
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < NB; ++j) request_v(buf[j], j);
 
     const int c = IDENT ? h : min(max(h2c[(size_t)b * H + h], 0), k - 1);
     const size_t crow = (size_t)b * k + c;
@@ -239,11 +257,12 @@ __global__ __launch_bounds__(kBlock) void value_kernel(const char *__restrict__ 
     float *prow = (probs_out != nullptr && (IDENT || rep[crow] == h)) ? probs_out + crow * T + t0 : nullptr;
 
     // the score this lane turns into a probability for batch `it` (lanes >= BATCH and rows past the end: none)
-    auto score_of = [&](int it) -> float {
-        const int tl = (it * kWaves + w) * TL::BATCH + lane;
-        return (lane < TL::BATCH && tl < n) ? srow[tl] : -INFINITY;
+    auto request_s = [&](Batch &bt, int it) {
+        const int tl = (it * NW + w) * TL::BATCH + lane;
+        bt.s = (it < n_it && lane < TL::BATCH && tl < n) ? srow[tl] : -INFINITY;
     };
-    float s_cur = n_it > 0 ? score_of(0) : -INFINITY;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) request_s(buf[j], j);
 
     const float2 *st = stats + crow * n_cs;
     float m = -INFINITY;
@@ -257,22 +276,13 @@ __global__ __launch_bounds__(kBlock) void value_kernel(const char *__restrict__ 
 #pragma unroll
     for (int e = 0; e < TL::EPL; ++e) acc[e] = 0.f;
 
-    for (int it = 0; it < n_it; ++it) {
-        // requests of the next batch
-        u32x4 nxt[kUnroll];
-        float s_nxt = -INFINITY;
-        if (it + 1 < n_it) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                nxt[u] = stream16(vbase + (size_t)min(batch_row<BF16>(it + 1, w, u, rg), n - 1) * TL::ROW_BYTES);
-            s_nxt = score_of(it + 1);
-        }
+    auto consume = [&](const Batch &bt, int it) {
         // probabilities of this batch: lane i < BATCH owns row i of the batch; slot rg*kUnroll + u holds the
         // row that lane group rg multiplies with its load u, so a lane reads kUnroll consecutive floats
-        const float p = expf(s_cur - M) * inv;          // exp(-inf) = 0 for rows past the end
+        const float p = expf(bt.s - M) * inv;          // exp(-inf) = 0 for rows past the end
         if (lane < TL::BATCH) {
             p_lds[w][(lane % TL::RPW) * kUnroll + lane / TL::RPW] = p;
-            const int tl = (it * kWaves + w) * TL::BATCH + lane;
+            const int tl = (it * NW + w) * TL::BATCH + lane;
             if (prow != nullptr && tl < n) prow[tl] = p;
         }
         __builtin_amdgcn_wave_barrier();
@@ -283,13 +293,23 @@ __global__ __launch_bounds__(kBlock) void value_kernel(const char *__restrict__ 
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u) {
             float f[TL::EPL];
-            unpack(cur[u], f);
+            unpack(bt.v[u], f);
 #pragma unroll
             for (int e = 0; e < TL::EPL; ++e) acc[e] = fmaf(pv[u], f[e], acc[e]);
         }
+    };
+
+    // NB batches are in flight; a buffer is refilled as soon as it has been consumed
+    for (int it0 = 0; it0 < n_it; it0 += NB) {
 #pragma unroll
-        for (int u = 0; u < kUnroll; ++u) cur[u] = nxt[u];
-        s_cur = s_nxt;
+        for (int j = 0; j < NB; ++j) {
+            const int it = it0 + j;
+            if (it < n_it) {
+                consume(buf[j], it);
+                request_v(buf[j], it + NB);
+                request_s(buf[j], it + NB);
+            }
+        }
     }
 
     // lane groups of a wave, then the waves
@@ -304,10 +324,12 @@ __global__ __launch_bounds__(kBlock) void value_kernel(const char *__restrict__ 
     }
     __syncthreads();
     if (tid < kHeadDim) {
-        const float val = (acc_lds[0][tid] + acc_lds[1][tid]) + (acc_lds[2][tid] + acc_lds[3][tid]);
+        float val = 0.f;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) val += acc_lds[i][tid];
         const size_t orow = (size_t)b * H + h;
         if (n_cp == 1) out[orow * kHeadDim + tid] = val;
-        else partial[(orow * n_cp + split) * kHeadDim + tid] = val;
+        else partial[(orow * n_cp + split) * kHeadDim + tid] = val;     // combine_kernel adds the rows up
     }
 }
 
@@ -334,27 +356,53 @@ struct Workspace {
     }
 };
 
+// Launches go through hipExtLaunchKernelGGL so that a caller who profiles can have the runtime stamp the begin
+// and the end of the kernel itself into a pair of events (both NULL for an ordinary launch).
 template <bool BF16, bool IDENT>
 int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap,
-                 float scale, const Workspace &w, const DecodePlan &pl, hipStream_t stream)
+                 float scale, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev, hipStream_t stream)
 {
-    score_kernel<BF16, IDENT><<<dim3(pl.n_cs, k, B), kBlock, 0, stream>>>(
-        static_cast<const char *>(q), static_cast<const char *>(kc), rep, H, k, T, Tc_cap, scale, pl.cs, pl.n_cs,
-        w.scores, w.stats);
+    hipExtLaunchKernelGGL((score_kernel<BF16, IDENT>), dim3(pl.n_cs, k, B), dim3(kBlock), 0, stream, ev.start, ev.stop,
+                          0, static_cast<const char *>(q), static_cast<const char *>(kc), rep, H, k, T, Tc_cap, scale,
+                          pl.cs, pl.n_cs, w.scores, w.stats);
+    return (int)hipGetLastError();
+}
+
+// A merge of the partial rows inside the value kernel (last workgroup of a head, found through a device-scope
+// arrival counter) was measured and dropped: with __threadfence() in every workgroup the kernel ran 10x slower
+// (L2 write-back + invalidate per fence across 8 XCDs), and with fence-free device-scope stores/loads it was
+// still slower than the separate combine launch at every chunk count tried.
+template <bool BF16, bool IDENT, int NW, int NB>
+int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
+                  float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
+                  hipStream_t stream)
+{
+    hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0, stream, ev.start,
+                          ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs, pl.cp, pl.n_cp,
+                          static_cast<const float *>(w.scores), static_cast<const float2 *>(w.stats), w.partial, out,
+                          probs_out);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || pl.n_cp == 1) return (int)e;
+    combine_kernel<<<dim3(B * H), kHeadDim, 0, stream>>>(w.partial, pl.n_cp, out);
     return (int)hipGetLastError();
 }
 
 template <bool BF16, bool IDENT>
 int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
-                 float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, hipStream_t stream)
+                 float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
+                 hipStream_t stream)
 {
-    value_kernel<BF16, IDENT><<<dim3(pl.n_cp, H, B), kBlock, 0, stream>>>(
-        static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs, pl.cp, pl.n_cp, w.scores, w.stats, w.partial,
-        out, probs_out);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.n_cp == 1) return (int)e;
-    combine_kernel<<<dim3(B * H), kHeadDim, 0, stream>>>(w.partial, pl.n_cp, out);
-    return (int)hipGetLastError();
+#ifdef CHAI_TUNING
+    const int nw = getenv("CHAI_NW") ? atoi(getenv("CHAI_NW")) : kValueWaves;
+    const int nb = getenv("CHAI_NB") ? atoi(getenv("CHAI_NB")) : kValueBatches;
+#define CHAI_VARIANT(NW_, NB_)                                                                                       \
+    if (nw == NW_ && nb == NB_)                                                                                        \
+        return values_launch<BF16, IDENT, NW_, NB_>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
+    CHAI_VARIANT(4, 2) CHAI_VARIANT(4, 3) CHAI_VARIANT(8, 2)
+#undef CHAI_VARIANT
+#endif
+    return values_launch<BF16, IDENT, kValueWaves, kValueBatches>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w,
+                                                                  pl, ev, stream);
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -369,11 +417,13 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
     for (int c : {256, 128}) {
         if ((long long)B * k * ((T + c - 1) / c) >= 1024) { pl.cs = c; break; }
     }
-    // value chunk: whole rows of the cache per workgroup while that gives >= 512 workgroups (2 per CU, all
-    // resident at once, no partial rows); otherwise the fewest chunks of >= 128 tokens that reach 512
+    // value chunk (measured on MI355X at T = 2048): with >= 384 heads one workgroup per head -- whole row of
+    // the cache, no partial rows, no combine launch -- is fastest (416 heads: 39 us against 41-44 us split);
+    // with fewer heads the single workgroups become latency-bound and splitting into >= 1024 workgroups wins
+    // even with the extra launch (288 heads: 30 us with 4 chunks against 34 us unsplit).
     {
         const long long heads = (long long)B * H > 0 ? (long long)B * H : 1;
-        long long want = heads >= 512 ? 1 : (512 + heads - 1) / heads;
+        long long want = heads >= 384 ? 1 : (1024 + heads - 1) / heads;
         const long long most = (T + 127) / 128;
         if (want > most) want = most;
         pl.cp = (int)(((T + want - 1) / want + 127) / 128 * 128);
@@ -398,26 +448,28 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
 }
 
 int launch_scores(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap, int dtype,
-                  float scale, void *workspace, const DecodePlan &plan, bool identity, hipStream_t stream)
-{
-    const Workspace w(workspace, plan);
-    if (dtype == CHAI_BF16)
-        return identity ? scores_typed<true, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, stream)
-                        : scores_typed<true, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, stream);
-    return identity ? scores_typed<false, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, stream)
-                    : scores_typed<false, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, stream);
-}
-
-int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
-                  int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
+                  float scale, void *workspace, const DecodePlan &plan, bool identity, const KernelEvents &ev,
                   hipStream_t stream)
 {
     const Workspace w(workspace, plan);
     if (dtype == CHAI_BF16)
-        return identity ? values_typed<true, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, stream)
-                        : values_typed<true, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, stream);
-    return identity ? values_typed<false, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, stream)
-                    : values_typed<false, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, stream);
+        return identity ? scores_typed<true, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream)
+                        : scores_typed<true, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream);
+    return identity ? scores_typed<false, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream)
+                    : scores_typed<false, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream);
+}
+
+int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
+                  int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
+                  const KernelEvents &ev, hipStream_t stream)
+{
+    const Workspace w(workspace, plan);
+    if (dtype == CHAI_BF16)
+        return identity
+                   ? values_typed<true, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream)
+                   : values_typed<true, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream);
+    return identity ? values_typed<false, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream)
+                    : values_typed<false, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream);
 }
 
 }  // namespace chai
