@@ -61,8 +61,8 @@ __global__ __launch_bounds__(64) void feature_kernel(const void *__restrict__ q5
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// K-Means: grid (B), one workgroup of 256 threads per batch row.  Dynamic LDS: centres [k][F] fp64, then
-// per-head distance [H] fp64, assignment/previous assignment [H], counts/labels [k].
+// K-Means: grid (B), one workgroup of 256 threads per batch row.  Dynamic LDS: centres [k][F] fp64, per-head
+// distance [H] fp64, slice winners [H][slices], assignment/previous assignment [H], counts/labels [k].
 // ---------------------------------------------------------------------------------------------------------
 __device__ __forceinline__ double sqdist(const float *__restrict__ x, const double *c, int F)
 {
@@ -77,16 +77,19 @@ __device__ __forceinline__ double sqdist(const float *__restrict__ x, const doub
 
 __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict__ feat, int H, int F, int k,
                                                         const int32_t *__restrict__ init_heads, int max_iter,
-                                                        int32_t *__restrict__ h2c, int32_t *__restrict__ rep,
-                                                        int32_t *__restrict__ ncl, int32_t *__restrict__ iters)
+                                                        int slices, int32_t *__restrict__ h2c,
+                                                        int32_t *__restrict__ rep, int32_t *__restrict__ ncl,
+                                                        int32_t *__restrict__ iters)
 {
     extern __shared__ double lds[];
-    double *centre = lds;                       // [k*F]
-    double *dmin = centre + (size_t)k * F;      // [H]
-    int *assign = reinterpret_cast<int *>(dmin + H);   // [H]
-    int *prev = assign + H;                     // [H]
-    int *count = prev + H;                      // [k]
-    int *label = count + k;                     // [k]
+    double *centre = lds;                                   // [k][F]
+    double *dmin = centre + (size_t)k * F;                  // [H]      distance of a head to its centre
+    double *cand_d = dmin + H;                              // [H][slices] best distance found by a slice
+    int *cand_j = reinterpret_cast<int *>(cand_d + (size_t)H * slices);   // [H][slices] and its centre
+    int *assign = cand_j + (size_t)H * slices;              // [H]
+    int *prev = assign + H;                                 // [H]
+    int *count = prev + H;                                  // [k]
+    int *label = count + k;                                 // [k]
     __shared__ int changed;
 
     const int b = blockIdx.x, tid = threadIdx.x;
@@ -103,14 +106,30 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
     int it = 0;
     for (;;) {
         ++it;
-        // assignment: one thread per head, centres in ascending order, strict '<' keeps the lowest on ties
-        for (int h = tid; h < H; h += kBlock) {
+        // Assignment.  The centres of a head are dealt to `slices` threads (slice s scans s, s+slices, ... in
+        // ascending order and keeps the first smallest), then one thread per head picks the smallest of the
+        // slice winners, the lowest centre on ties: the same centre a single ascending scan would pick.  Each
+        // distance is one sequential fp64 sum inside one thread.
+        for (int p = tid; p < H * slices; p += kBlock) {
+            const int h = p / slices, sl = p - h * slices;
             const float *x = X + (size_t)h * F;
-            int best = 0;
-            double bd = sqdist(x, centre, F);
-            for (int j = 1; j < k; ++j) {
+            int best = -1;
+            double bd = 0.0;
+            for (int j = sl; j < k; j += slices) {
                 const double dj = sqdist(x, centre + (size_t)j * F, F);
-                if (dj < bd) { bd = dj; best = j; }
+                if (best < 0 || dj < bd) { bd = dj; best = j; }
+            }
+            cand_d[p] = bd;
+            cand_j[p] = best;
+        }
+        __syncthreads();
+        for (int h = tid; h < H; h += kBlock) {
+            int best = cand_j[(size_t)h * slices];
+            double bd = cand_d[(size_t)h * slices];
+            for (int sl = 1; sl < slices; ++sl) {
+                const int j = cand_j[(size_t)h * slices + sl];
+                const double dj = cand_d[(size_t)h * slices + sl];
+                if (j >= 0 && (dj < bd || (dj == bd && j < best))) { bd = dj; best = j; }
             }
             assign[h] = best;
             dmin[h] = bd;
@@ -119,7 +138,8 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
         if (tid == 0) {
             for (int j = 0; j < k; ++j) count[j] = 0;
             for (int h = 0; h < H; ++h) count[assign[h]]++;
-            // repair of centres that received no head, in ascending order
+            // centres that received no head take, in ascending order, the farthest head of a cluster that can
+            // spare one
             for (int j = 0; j < k; ++j) {
                 if (count[j] != 0) continue;
                 int pick = -1;
@@ -171,6 +191,14 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
     }
 }
 
+// threads that share the centres of one head: as many as fit the workgroup, at most one per centre
+int assignment_slices(int H, int k)
+{
+    int s = kBlock / H;
+    if (s > k) s = k;
+    return s < 1 ? 1 : s;
+}
+
 }  // namespace
 
 int launch_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int dtype, int64_t qs, int64_t ks,
@@ -183,14 +211,15 @@ int launch_score_features(const void *q5, const void *k5, int B, int H, int n_to
 
 size_t assign_clusters_lds_bytes(int H, int F, int k)
 {
-    return sizeof(double) * ((size_t)k * F + H) + sizeof(int) * (2 * (size_t)H + 2 * (size_t)k);
+    const size_t sl = (size_t)assignment_slices(H, k);
+    return sizeof(double) * ((size_t)k * F + H + H * sl) + sizeof(int) * (H * sl + 2 * (size_t)H + 2 * (size_t)k);
 }
 
 int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const int32_t *init_heads, int max_iter,
                            int32_t *h2c, int32_t *rep, int32_t *ncl, int32_t *iters, hipStream_t stream)
 {
-    kmeans_kernel<<<dim3(B), kBlock, assign_clusters_lds_bytes(H, F, k), stream>>>(feat, H, F, k, init_heads,
-                                                                                  max_iter, h2c, rep, ncl, iters);
+    kmeans_kernel<<<dim3(B), kBlock, assign_clusters_lds_bytes(H, F, k), stream>>>(
+        feat, H, F, k, init_heads, max_iter, assignment_slices(H, k), h2c, rep, ncl, iters);
     return (int)hipGetLastError();
 }
 
