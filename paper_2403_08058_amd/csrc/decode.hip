@@ -21,8 +21,6 @@ namespace {
 constexpr int kUnroll = 8;        // 16-byte loads per lane in one batch
 constexpr int kMaxCs = 256;       // largest score chunk (= workgroup size: one thread per score)
 constexpr int kWaves = kBlock / 64;   // waves per workgroup of the score kernel
-constexpr int kValueWaves = 4;    // waves per workgroup of the value kernel
-constexpr int kValueBatches = 2;  // batches each wave of the value kernel keeps in flight
 
 template <bool BF16>
 struct Tile {
@@ -202,14 +200,15 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
 // Every wave works on its own: it merges the chunk statistics of its cluster into the row maximum M and the
 // denominator (exact merge of the chunks), and then, batch by batch, its first BATCH lanes turn one score
 // each into a final probability exp(s - M) / denominator, hand them to the other lanes through a private
-// LDS strip, and all lanes accumulate p * V for the rows they loaded.  The loads of the next batch (V rows
-// and scores) are issued before the current batch is consumed, and the first batch is requested before the
-// statistics are merged, so the stream never drains; the only workgroup barrier is the one that adds up the
-// four waves at the end.  With one chunk per head the sum goes to `out`, otherwise to a partial row that
+// LDS strip, and all lanes accumulate p * V for the rows they loaded.  Each wave keeps NB batches (V rows and
+// scores) in flight -- a buffer is refilled right after it is consumed -- and the first ones are requested
+// before the statistics are merged; with NW independent waves per workgroup the stream never drains.  The
+// only workgroup barrier is the one that adds up the waves at the end.  With one chunk per head the sum goes to `out`, otherwise to a partial row that
 // combine_kernel adds up in chunk order.
 // ---------------------------------------------------------------------------------------------------------
-template <bool BF16, bool IDENT, int NW, int NB>
-__global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__ v, const int32_t *__restrict__ h2c,
+template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P>
+__global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__ v,
+                                                        const int32_t *__restrict__ h2c,
                                                         const int32_t *__restrict__ rep, int H, int k, int T,
                                                         int T_cap, int n_cs, int cp, int n_cp,
                                                         const float *__restrict__ scores,
@@ -230,7 +229,9 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     const int n_batches = (n + TL::BATCH - 1) / TL::BATCH;
     const int n_it = n_batches > w ? (n_batches - w + NW - 1) / NW : 0;     // batches of this wave
 
-    const char *vbase = v + (((size_t)b * H + h) * T_cap + t0) * TL::ROW_BYTES + cg * 16;
+    // uniform base of the chunk + a 32-bit per-lane byte offset (a chunk is far below 4 GiB)
+    const char *vbase = v + (((size_t)b * H + h) * T_cap + t0) * TL::ROW_BYTES;
+    const unsigned int lane_off = cg * 16;
 
     // one batch: the 16-byte pieces of kUnroll * RPW consecutive rows, and (lanes < BATCH) one row's score
     struct Batch {
@@ -239,14 +240,15 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     };
     Batch buf[NB];
 
-    // rows of batch `it` of this wave start at (it * NW + w) * BATCH within the chunk
+    // Rows of batch `it` of this wave start at (it * NW + w) * BATCH within the chunk.  Every batch issues the
+    // same number of loads whatever `it` is -- rows past the end are clamped to the last row and later
+    // multiplied by p = 0 -- so the compiler can wait for exactly the batch it consumes and leave the younger
+    // ones in flight (loads under a condition would force it to drain the whole queue at every merge point).
     auto request_v = [&](Batch &bt, int it) {
-        if (it < n_it) {
-            const int r0 = (it * NW + w) * TL::BATCH + rg;
+        const int r0 = (it * NW + w) * TL::BATCH + rg;
 #pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                bt.v[u] = stream16(vbase + (size_t)min(r0 + u * TL::RPW, n - 1) * TL::ROW_BYTES);
-        }
+        for (int u = 0; u < kUnroll; ++u)
+            bt.v[u] = stream16(vbase + ((unsigned int)min(r0 + u * TL::RPW, n - 1) * TL::ROW_BYTES + lane_off));
     };
 #pragma unroll
     for (int j = 0; j < NB; ++j) request_v(buf[j], j);
@@ -254,12 +256,14 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     const int c = IDENT ? h : min(max(h2c[(size_t)b * H + h], 0), k - 1);
     const size_t crow = (size_t)b * k + c;
     const float *srow = scores + crow * T + t0;
-    float *prow = (probs_out != nullptr && (IDENT || rep[crow] == h)) ? probs_out + crow * T + t0 : nullptr;
+    float *prow = nullptr;
+    if (WRITE_P) prow = (probs_out != nullptr && (IDENT || rep[crow] == h)) ? probs_out + crow * T + t0 : nullptr;
 
-    // the score this lane turns into a probability for batch `it` (lanes >= BATCH and rows past the end: none)
+    // the score this lane turns into a probability for batch `it` (lanes >= BATCH and rows past the end: none;
+    // they still issue the load, of the last score, to keep the count fixed)
     auto request_s = [&](Batch &bt, int it) {
         const int tl = (it * NW + w) * TL::BATCH + lane;
-        bt.s = (it < n_it && lane < TL::BATCH && tl < n) ? srow[tl] : -INFINITY;
+        bt.s = srow[min(tl, n - 1)];          // masked when it is consumed
     };
 #pragma unroll
     for (int j = 0; j < NB; ++j) request_s(buf[j], j);
@@ -279,11 +283,13 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     auto consume = [&](const Batch &bt, int it) {
         // probabilities of this batch: lane i < BATCH owns row i of the batch; slot rg*kUnroll + u holds the
         // row that lane group rg multiplies with its load u, so a lane reads kUnroll consecutive floats
-        const float p = expf(bt.s - M) * inv;          // exp(-inf) = 0 for rows past the end
+        const int tl = (it * NW + w) * TL::BATCH + lane;
+        const float p = tl < n ? expf(bt.s - M) * inv : 0.f;          // rows past the end weigh nothing
         if (lane < TL::BATCH) {
             p_lds[w][(lane % TL::RPW) * kUnroll + lane / TL::RPW] = p;
-            const int tl = (it * NW + w) * TL::BATCH + lane;
-            if (prow != nullptr && tl < n) prow[tl] = p;
+            if (WRITE_P) {
+                if (prow != nullptr && tl < n) prow[tl] = p;
+            }
         }
         __builtin_amdgcn_wave_barrier();
         float pv[kUnroll];
@@ -299,16 +305,14 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
         }
     };
 
-    // NB batches are in flight; a buffer is refilled as soon as it has been consumed
+    // NB batches are in flight; a buffer is refilled as soon as it has been consumed.  The trip count is
+    // rounded up to a multiple of NB: the surplus batches lie past the end and contribute p = 0.
     for (int it0 = 0; it0 < n_it; it0 += NB) {
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
-            const int it = it0 + j;
-            if (it < n_it) {
-                consume(buf[j], it);
-                request_v(buf[j], it + NB);
-                request_s(buf[j], it + NB);
-            }
+            consume(buf[j], it0 + j);
+            request_v(buf[j], it0 + j + NB);
+            request_s(buf[j], it0 + j + NB);
         }
     }
 
@@ -377,10 +381,18 @@ int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
                   float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
                   hipStream_t stream)
 {
-    hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0, stream, ev.start,
-                          ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs, pl.cp, pl.n_cp,
-                          static_cast<const float *>(w.scores), static_cast<const float2 *>(w.stats), w.partial, out,
-                          probs_out);
+    // the copy of the probabilities (tests, inspection) lives in an instantiation of its own so that the
+    // production kernel has no store inside its streaming loop
+    if (probs_out != nullptr)
+        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, true>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0, stream,
+                              ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs,
+                              pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
+                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out);
+    else
+        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, false>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0, stream,
+                              ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs,
+                              pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
+                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.n_cp == 1) return (int)e;
     combine_kernel<<<dim3(B * H), kHeadDim, 0, stream>>>(w.partial, pl.n_cp, out);
@@ -392,17 +404,22 @@ int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, i
                  float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
                  hipStream_t stream)
 {
+    // Workgroup shape (measured on MI355X): eight waves with one batch in flight each are 1-6 % faster than
+    // four waves with two batches up to a few thousand tokens per workgroup; on long chunks four waves with
+    // two batches are ~1.5 % ahead.
+    int nw = pl.cp >= 4096 ? 4 : 8;
+    int nb = pl.cp >= 4096 ? 2 : 1;
 #ifdef CHAI_TUNING
-    const int nw = getenv("CHAI_NW") ? atoi(getenv("CHAI_NW")) : kValueWaves;
-    const int nb = getenv("CHAI_NB") ? atoi(getenv("CHAI_NB")) : kValueBatches;
-#define CHAI_VARIANT(NW_, NB_)                                                                                       \
-    if (nw == NW_ && nb == NB_)                                                                                        \
-        return values_launch<BF16, IDENT, NW_, NB_>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
-    CHAI_VARIANT(4, 2) CHAI_VARIANT(4, 3) CHAI_VARIANT(8, 2)
-#undef CHAI_VARIANT
+    if (getenv("CHAI_NW")) nw = atoi(getenv("CHAI_NW"));
+    if (getenv("CHAI_NB")) nb = atoi(getenv("CHAI_NB"));
+    if (nw == 4 && nb == 3)
+        return values_launch<BF16, IDENT, 4, 3>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
+    if (nw == 16 && nb == 1)
+        return values_launch<BF16, IDENT, 16, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
 #endif
-    return values_launch<BF16, IDENT, kValueWaves, kValueBatches>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w,
-                                                                  pl, ev, stream);
+    if (nw == 4 && nb == 2)
+        return values_launch<BF16, IDENT, 4, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
+    return values_launch<BF16, IDENT, 8, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
