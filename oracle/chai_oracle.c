@@ -266,6 +266,63 @@ static double sqdist(const float *x, const double *c, int F)
 }
 
 /*
+ * Clustering error of a partition (Section 3.2: sum of squared distances of
+ * the points to the centre of their cluster), with every non-empty
+ * cluster's centre at the mean of its members.  `mean` is scratch of F
+ * doubles.  Clusters in label order, members in head order, one running sum.
+ */
+static double partition_error(const float *X, const int32_t *label_of, int H, int F, int k, double *mean)
+{
+    double total = 0.0;
+    for (int j = 0; j < k; ++j) {
+        int cnt = 0;
+        for (int h = 0; h < H; ++h)
+            if (label_of[h] == j) ++cnt;
+        if (cnt == 0) continue;
+        for (int f = 0; f < F; ++f) {
+            double acc = 0.0;
+            for (int h = 0; h < H; ++h)
+                if (label_of[h] == j) acc = acc + (double)X[(int64_t)h * F + f];
+            mean[f] = acc / (double)cnt;
+        }
+        for (int h = 0; h < H; ++h)
+            if (label_of[h] == j) total += sqdist(X + (int64_t)h * F, mean, F);
+    }
+    return total;
+}
+
+int chai_oracle_cluster_error(const float *feat, const int32_t *head_to_cluster, int B, int H, int F, int k,
+                              double *sse)
+{
+    if (!feat || !head_to_cluster || !sse) return 1;
+    if (B < 0 || H < 1 || F < 1 || k < 1 || k > H) return 2;
+    double *mean = (double *)malloc(sizeof(double) * (size_t)F);
+    for (int b = 0; b < B; ++b)
+        sse[b] = partition_error(feat + (int64_t)b * H * F, head_to_cluster + (int64_t)b * H, H, F, k, mean);
+    free(mean);
+    return 0;
+}
+
+/*
+ * Number of clusters from the error curve (Section 3.2: "choose the number
+ * of clusters when the error plateaus"; the paper reads the elbow plot by
+ * eye).  Reading used here: with err[i] the mean clustering error at ks[i]
+ * (ks ascending), pick the smallest ks[i] whose error has come down to
+ * within a fraction `tol` of the whole drop,
+ *     err[i] - err[n-1] <= tol * (err[0] - err[n-1]).
+ */
+int chai_oracle_pick_cluster_count(const double *err, const int32_t *ks, int n, double tol, int32_t *k_out)
+{
+    if (!err || !ks || !k_out) return 1;
+    if (n < 1 || !(tol >= 0.0)) return 2;
+    double drop = err[0] - err[n - 1];
+    for (int i = 0; i < n; ++i)
+        if (err[i] - err[n - 1] <= tol * drop) { *k_out = ks[i]; return 0; }
+    *k_out = ks[n - 1];
+    return 0;
+}
+
+/*
  * Cluster membership by K-Means (Section 3.5: K-Means on the observed
  * activations once five tokens are processed; Section 3.2: the clustering
  * error is the sum of squared distances to the closest centre, i.e. the
@@ -382,26 +439,7 @@ int chai_oracle_kmeans(const float *feat, int B, int H, int F, int k, const int3
         n_clusters[b] = n;
         if (iters) iters[b] = it;
 
-        if (sse) {
-            /* clustering error of the returned partition */
-            double total = 0.0;
-            for (int j = 0; j < n; ++j) {
-                int cnt = 0;
-                for (int h = 0; h < H; ++h)
-                    if (head_to_cluster[(int64_t)b * H + h] == j) ++cnt;
-                for (int f = 0; f < F; ++f) {
-                    double acc = 0.0;
-                    for (int h = 0; h < H; ++h)
-                        if (head_to_cluster[(int64_t)b * H + h] == j)
-                            acc = acc + (double)X[(int64_t)h * F + f];
-                    centre[f] = acc / (double)cnt;
-                }
-                for (int h = 0; h < H; ++h)
-                    if (head_to_cluster[(int64_t)b * H + h] == j)
-                        total += sqdist(X + (int64_t)h * F, centre, F);
-            }
-            sse[b] = total;
-        }
+        if (sse) sse[b] = partition_error(X, head_to_cluster + (int64_t)b * H, H, F, k, centre);
     }
     free(centre); free(dmin); free(assign); free(prev); free(count); free(label);
     return 0;

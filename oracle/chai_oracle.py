@@ -41,6 +41,8 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.chai_oracle_dense_decode.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cd, vp, vp]
     L.chai_oracle_score_features.argtypes = [vp, vp, ci, ci, ci, ci, ci, i64, i64, cd, vp]
     L.chai_oracle_kmeans.argtypes = [vp, ci, ci, ci, ci, i32p, ci, i32p, i32p, i32p, i32p, vp]
+    L.chai_oracle_cluster_error.argtypes = [vp, i32p, ci, ci, ci, ci, vp]
+    L.chai_oracle_pick_cluster_count.argtypes = [vp, i32p, ci, cd, vp]
     L.chai_oracle_compact_kcache.argtypes = [vp, i32p, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     L.chai_oracle_append_kv.argtypes = [vp, vp, i32p, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci]
     return L
@@ -164,6 +166,24 @@ def kmeans(feat, init_heads, max_iter=50, want_sse=False):
                                   _p(sse))
     _check(rc, "kmeans")
     return (h2c, rep, ncl, its, sse) if want_sse else (h2c, rep, ncl, its)
+
+
+def cluster_error(feat, head_to_cluster, k):
+    """Sum of squared distances of every head's features to the mean of its cluster; [B] f64."""
+    feat = _c(feat, np.float32)
+    h2c = _c(head_to_cluster, np.int32)
+    B, H, F = feat.shape
+    sse = np.empty((B,), np.float64)
+    _check(lib().chai_oracle_cluster_error(_p(feat), _p(h2c), B, H, F, int(k), _p(sse)), "cluster_error")
+    return sse
+
+
+def pick_cluster_count(err, ks, tol):
+    err = _c(err, np.float64)
+    ks = _c(ks, np.int32)
+    out = np.zeros((1,), np.int32)
+    _check(lib().chai_oracle_pick_cluster_count(_p(err), _p(ks), len(ks), float(tol), _p(out)), "pick_cluster_count")
+    return int(out[0])
 
 
 def compact_kcache(k_full, rep_heads, T, Tc_cap=None, k_compact=None, want_src_rows=False):

@@ -392,6 +392,43 @@ def pin_kmeans_recovers_planted_features():
             assert int(n[b]) == cfg.ks[layer]
 
 
+def pin_cluster_error_and_count():
+    gd = _golden("cluster_count_worked.json")
+    for c in gd["error_cases"]:
+        X = np.asarray(c["feat"], np.float32)[None]
+        lab = np.asarray(c["labels"], np.int32)[None]
+        assert abs(O.cluster_error(X, lab, c["k"])[0] - c["sse"]) < 1e-12, c["how"]
+    for c in gd["pick_cases"]:
+        assert O.pick_cluster_count(c["err"], c["ks"], c["tol"]) == c["k"], c["how"]
+    # against numpy on random partitions with arbitrary labels; extremes k = H and k = 1
+    g = np.random.default_rng(700)
+    B, H, F = 4, 32, 25
+    X = g.random((B, H, F)).astype(np.float32)
+    lab = g.integers(0, 11, size=(B, H)).astype(np.int32)
+    e = O.cluster_error(X, lab, 11)
+    for b in range(B):
+        assert abs(e[b] - _sse(X[b], lab[b])) < 1e-10
+    assert np.all(O.cluster_error(X, np.tile(np.arange(H, dtype=np.int32), (B, 1)), H) == 0.0)
+    one = O.cluster_error(X, np.zeros((B, H), np.int32), 1)
+    assert np.allclose(one, [H * X[b].astype(np.float64).var(axis=0).sum() for b in range(B)], rtol=1e-12)
+    # the error curve of planted groups falls to its plateau at the planted count
+    kk, ks = 6, [1, 2, 3, 4, 6, 8, 12, 16]
+    groups = W.planted_partition(g, B, H, kk)
+    cent = g.standard_normal((B, kk, F))
+    Xp = np.stack([cent[b, groups[b]] for b in range(B)]) + 0.01 * g.standard_normal((B, H, F))
+    Xp = Xp.astype(np.float32)
+    curve = []
+    for k_try in ks:
+        init = W.one_head_per_group(g, groups, kk)[:, :k_try] if k_try <= kk else np.concatenate(
+            [W.one_head_per_group(g, groups, kk),
+             np.stack([g.choice(np.setdiff1d(np.arange(H), W.one_head_per_group(g, groups, kk)[b]), k_try - kk,
+                                replace=False) for b in range(B)])], axis=1)
+        h2c, _, _, _ = O.kmeans(Xp, init.astype(np.int32))
+        curve.append(O.cluster_error(Xp, h2c, k_try).mean())
+    assert all(curve[i + 1] <= curve[i] + 1e-9 for i in range(len(ks) - 1))
+    assert O.pick_cluster_count(curve, ks, 0.02) == kk
+
+
 # ----------------------------------------------------------------------------------------------
 # cache pins
 # ----------------------------------------------------------------------------------------------

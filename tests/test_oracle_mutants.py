@@ -60,6 +60,14 @@ MUTANTS = [
      ["pin_kmeans_worked_examples"]),
     ("kmeans_single_pass", "if (!changed || it >= max_iter) break;", "if (!changed || it >= 1) break;", 0,
      ["pin_kmeans_worked_examples"]),
+    ("cluster_error_mean_over_all_heads", "mean[f] = acc / (double)cnt;", "mean[f] = acc / (double)H;", 0,
+     ["pin_cluster_error_and_count"]),
+    ("cluster_error_distance_not_squared_sum", "if (label_of[h] == j) total += sqdist(X + (int64_t)h * F, mean, F);",
+     "if (label_of[h] == j) total += sqrt(sqdist(X + (int64_t)h * F, mean, F));", 0, ["pin_cluster_error_and_count"]),
+    ("cluster_count_measured_from_first_point", "if (err[i] - err[n - 1] <= tol * drop)", "if (err[0] - err[i] >= tol * drop)", 0,
+     ["pin_cluster_error_and_count"]),
+    ("cluster_count_returns_index", "{ *k_out = ks[i]; return 0; }", "{ *k_out = i; return 0; }", 0,
+     ["pin_cluster_error_and_count"]),
     ("compaction_source_stride", "int64_t src = ((int64_t)b * H + r) * T_cap + t;", "int64_t src = ((int64_t)b * H + r) * Tc_cap + t;", 0,
      ["pin_compaction_is_a_gather"]),
     ("compaction_copies_cluster_id_head", "int64_t src = ((int64_t)b * H + r) * T_cap + t;", "int64_t src = ((int64_t)b * H + j) * T_cap + t;", 0,
