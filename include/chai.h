@@ -119,6 +119,32 @@ int chai_assign_clusters(const float *feat, int B, int H, int F, int k, const in
                          int32_t *n_clusters, int32_t *iters, void *stream);
 
 /*
+ * Offline choice of the number of clusters (Section 3.2: clustering error =
+ * sum of squared distances to the closest centre, plotted against the number
+ * of clusters; the count is taken where the error plateaus).
+ *
+ * chai_cluster_error: for each batch row (one sample) the error of the given
+ * partition, every non-empty cluster's centre at the mean of its members;
+ * fp64, clusters in label order, heads ascending, one running sum (bit-
+ * identical to the sequential evaluation).
+ *   feat [B,H,F] fp32; head_to_cluster [B,H] int32 with labels in [0,k) (any
+ *   labelling, labels may be unused); sse [B] fp64 on the device, written.
+ *   Limits as for chai_assign_clusters.
+ * A sweep is the caller's loop: for each candidate k, chai_assign_clusters
+ * then chai_cluster_error over the samples.
+ *
+ * chai_pick_cluster_count (HOST pointers, runs on the host, no GPU work):
+ * mean_error[i] is the error averaged over the samples at ks[i], ks strictly
+ * ascending.  The paper reads the elbow by eye; the rule here returns the
+ * smallest ks[i] with  mean_error[i] - mean_error[n-1] <= tol * (mean_error[0]
+ * - mean_error[n-1]),  i.e. whose error has come within a fraction tol of the
+ * whole drop.
+ */
+int chai_cluster_error(const float *feat, const int32_t *head_to_cluster, int B, int H, int F, int k,
+                       double *sse, void *stream);
+int chai_pick_cluster_count(const double *mean_error, const int32_t *ks, int n, double tol, int32_t *k_out);
+
+/*
  * K-cache pruning (Section 3.5: once membership is fixed, the keys of the
  * pruned heads are removed; Section 4.3 / Fig. 3: all values are kept).
  *   k_compact[b][j][t][:] = k_full[b][rep_heads[b][j]][t][:]   for t < T.

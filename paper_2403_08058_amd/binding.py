@@ -22,6 +22,7 @@ STATUS_NAMES = {0: "CHAI_OK", 1: "CHAI_ERR_NULL", 2: "CHAI_ERR_SHAPE", 3: "CHAI_
                 5: "CHAI_ERR_UNSUPPORTED", 6: "CHAI_ERR_HIP", 7: "CHAI_ERR_ALIGN"}
 
 EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_assign_clusters",
+           "chai_cluster_error", "chai_pick_cluster_count",
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention",
            "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
            "chai_dense_decode_attention"]
@@ -45,6 +46,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_status_string.argtypes = [ci]
     L.chai_score_features.argtypes = [vp, vp, ci, ci, ci, ci, ci, i64, i64, cf, vp, vp]
     L.chai_assign_clusters.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp, vp, vp, vp, vp]
+    L.chai_cluster_error.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+    L.chai_pick_cluster_count.argtypes = [vp, vp, ci, ctypes.c_double, vp]
     L.chai_compact_kcache.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     L.chai_append_kv.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     L.chai_decode_workspace_bytes.restype = sz
@@ -132,6 +135,26 @@ def chai_assign_clusters(feat, init_heads, max_iter: int = 50, head_to_cluster=N
            _lib.chai_assign_clusters(_ptr(feat), B, H, F, k, _ptr(init_heads), max_iter, _ptr(head_to_cluster),
                                      _ptr(rep_heads), _ptr(n_clusters), _ptr(iters), _stream(stream)))
     return head_to_cluster, rep_heads, n_clusters, iters
+
+
+def chai_cluster_error(feat, head_to_cluster, k: int, sse=None, stream=None):
+    """feat [B,H,F] fp32, head_to_cluster [B,H] int32 -> sse [B] fp64 (device)."""
+    B, H, F = feat.shape
+    if sse is None:
+        sse = torch.empty((B,), dtype=torch.float64, device=feat.device)
+    _check("chai_cluster_error",
+           _lib.chai_cluster_error(_ptr(feat), _ptr(head_to_cluster), B, H, F, k, _ptr(sse), _stream(stream)))
+    return sse
+
+
+def chai_pick_cluster_count(mean_error, ks, tol: float) -> int:
+    """Host-side plateau rule on an error curve (sequences of floats / ints)."""
+    n = len(ks)
+    err = (ctypes.c_double * n)(*[float(e) for e in mean_error])
+    kk = (ctypes.c_int32 * n)(*[int(k) for k in ks])
+    out = ctypes.c_int32(0)
+    _check("chai_pick_cluster_count", _lib.chai_pick_cluster_count(err, kk, n, float(tol), ctypes.byref(out)))
+    return int(out.value)
 
 
 def chai_compact_kcache(k_full, rep_heads, k_compact, T: int, stream=None):

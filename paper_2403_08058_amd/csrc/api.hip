@@ -95,6 +95,33 @@ int chai_assign_clusters(const float *feat, int B, int H, int F, int k, const in
                                              n_clusters, iters, static_cast<hipStream_t>(stream)));
 }
 
+int chai_cluster_error(const float *feat, const int32_t *head_to_cluster, int B, int H, int F, int k, double *sse,
+                       void *stream)
+{
+    if (!feat || !head_to_cluster || !sse) return CHAI_ERR_NULL;
+    if (B < 0 || H < 1 || F < 1 || k < 1 || k > H) return CHAI_ERR_SHAPE;
+    if (H > 256 || F > 64 || (long long)k * F > 7168) return CHAI_ERR_UNSUPPORTED;
+    if (cluster_error_lds_bytes(H, F, k) > 64 * 1024 - 64) return CHAI_ERR_UNSUPPORTED;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_cluster_error(feat, head_to_cluster, B, H, F, k, sse, static_cast<hipStream_t>(stream)));
+}
+
+int chai_pick_cluster_count(const double *mean_error, const int32_t *ks, int n, double tol, int32_t *k_out)
+{
+    if (!mean_error || !ks || !k_out) return CHAI_ERR_NULL;
+    if (n < 1 || !(tol >= 0.0)) return CHAI_ERR_SHAPE;
+    for (int i = 1; i < n; ++i)
+        if (ks[i] <= ks[i - 1]) return CHAI_ERR_SHAPE;
+    const double floor_err = mean_error[n - 1];
+    const double slack = tol * (mean_error[0] - floor_err);
+    int pick = ks[n - 1];
+    for (int i = 0; i < n; ++i) {
+        if (mean_error[i] - floor_err <= slack) { pick = ks[i]; break; }
+    }
+    *k_out = pick;
+    return CHAI_OK;
+}
+
 int chai_compact_kcache(const void *k_full, const int32_t *rep_heads, void *k_compact, int B, int H, int k, int T,
                         int T_cap, int Tc_cap, int d, int dtype, void *stream)
 {

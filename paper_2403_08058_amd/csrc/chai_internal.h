@@ -46,6 +46,10 @@ int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const 
                            int32_t *h2c, int32_t *rep, int32_t *ncl, int32_t *iters, hipStream_t stream);
 size_t assign_clusters_lds_bytes(int H, int F, int k);
 
+int launch_cluster_error(const float *feat, const int32_t *h2c, int B, int H, int F, int k, double *sse,
+                         hipStream_t stream);
+size_t cluster_error_lds_bytes(int H, int F, int k);
+
 int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
                           int T_cap, int Tc_cap, int dtype, hipStream_t stream);
 

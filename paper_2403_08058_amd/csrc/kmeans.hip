@@ -191,6 +191,53 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
     }
 }
 
+// ---------------------------------------------------------------------------------------------------------
+// Clustering error of a given partition (Section 3.2): grid (B), 256 threads.  Means per (cluster, coordinate)
+// by one thread each (members in head order), distance of every head to its cluster's mean by one thread each,
+// then thread 0 adds the distances cluster by cluster, heads ascending: the order of the sequential statement.
+// Dynamic LDS: means [k][F] fp64, distances [H] fp64, counts [k].
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void cluster_error_kernel(const float *__restrict__ feat,
+                                                               const int32_t *__restrict__ h2c, int H, int F, int k,
+                                                               double *__restrict__ sse)
+{
+    extern __shared__ double lds[];
+    double *mean = lds;                          // [k][F]
+    double *dist = mean + (size_t)k * F;         // [H]
+    int *count = reinterpret_cast<int *>(dist + H);   // [k]
+    const int b = blockIdx.x, tid = threadIdx.x;
+    const float *X = feat + (size_t)b * H * F;
+    const int32_t *lab = h2c + (size_t)b * H;
+
+    for (int j = tid; j < k; j += kBlock) {
+        int c = 0;
+        for (int h = 0; h < H; ++h) c += lab[h] == j;
+        count[j] = c;
+    }
+    __syncthreads();
+    for (int i = tid; i < k * F; i += kBlock) {
+        const int j = i / F, f = i - j * F;
+        if (count[j] == 0) continue;
+        double acc = 0.0;
+        for (int h = 0; h < H; ++h)
+            if (lab[h] == j) acc = acc + (double)X[(size_t)h * F + f];
+        mean[i] = acc / (double)count[j];
+    }
+    __syncthreads();
+    for (int h = tid; h < H; h += kBlock) {
+        const int j = lab[h];
+        dist[h] = (j >= 0 && j < k) ? sqdist(X + (size_t)h * F, mean + (size_t)j * F, F) : 0.0;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        double total = 0.0;
+        for (int j = 0; j < k; ++j)
+            for (int h = 0; h < H; ++h)
+                if (lab[h] == j) total += dist[h];
+        sse[b] = total;
+    }
+}
+
 // threads that share the centres of one head: as many as fit the workgroup, at most one per centre
 int assignment_slices(int H, int k)
 {
@@ -220,6 +267,18 @@ int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const 
 {
     kmeans_kernel<<<dim3(B), kBlock, assign_clusters_lds_bytes(H, F, k), stream>>>(
         feat, H, F, k, init_heads, max_iter, assignment_slices(H, k), h2c, rep, ncl, iters);
+    return (int)hipGetLastError();
+}
+
+size_t cluster_error_lds_bytes(int H, int F, int k)
+{
+    return sizeof(double) * ((size_t)k * F + H) + sizeof(int) * (size_t)k;
+}
+
+int launch_cluster_error(const float *feat, const int32_t *h2c, int B, int H, int F, int k, double *sse,
+                         hipStream_t stream)
+{
+    cluster_error_kernel<<<dim3(B), kBlock, cluster_error_lds_bytes(H, F, k), stream>>>(feat, h2c, H, F, k, sse);
     return (int)hipGetLastError();
 }
 

@@ -24,7 +24,7 @@ def declared_functions():
 
 def test_header_symbols_exported(chai):
     names = declared_functions()
-    assert len(names) == 13 and "chai_assign_clusters" in names and "chai_compact_kcache" in names \
+    assert len(names) == 15 and "chai_assign_clusters" in names and "chai_compact_kcache" in names \
         and "chai_decode_attention" in names
     L = ctypes.CDLL(chai.LIB_PATH)
     for n in names:
@@ -80,6 +80,18 @@ def test_argument_checks_run_before_any_launch(chai):
     assert L.chai_assign_clusters(fake, 0, 32, 25, 8, fake, 50, fake, fake, fake, None, None) == 0  # B = 0: no-op
     assert L.chai_score_features(fake, fake, 1, 32, 9, 128, 1, 9 * 128, 9 * 128, 0.1, fake, None) == 5
     assert L.chai_score_features(fake, fake, 1, 32, 5, 128, 1, 4 * 128, 5 * 128, 0.1, fake, None) == 2
+
+
+def test_pick_cluster_count_runs_on_the_host(chai):
+    """The plateau rule is host code with host pointers: checked here against the hand-worked cases."""
+    import json
+    cases = json.load(open(os.path.join(ROOT, "tests", "golden", "cluster_count_worked.json")))["pick_cases"]
+    for c in cases:
+        assert chai.chai_pick_cluster_count(c["err"], c["ks"], c["tol"]) == c["k"], c["how"]
+    with pytest.raises(chai.ChaiError):
+        chai.chai_pick_cluster_count([3.0, 2.0], [4, 4], 0.1)        # ks not ascending
+    with pytest.raises(chai.ChaiError):
+        chai.chai_pick_cluster_count([3.0, 2.0], [2, 4], -1.0)
 
 
 def test_product_does_not_import_the_oracle():

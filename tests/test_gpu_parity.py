@@ -299,6 +299,40 @@ def test_assign_clusters_on_feature_like_data():
         assert np.array_equal(ncl.cpu().numpy(), ncl_o) and np.array_equal(it.cpu().numpy(), it_o)
 
 
+def test_cluster_error_bit_exact_and_sweep():
+    """Clustering error of a partition: same fp64 bits as the oracle; and the offline sweep over candidate
+    cluster counts (k-means + error per sample, plateau rule on the mean curve) finds the planted count."""
+    g = np.random.default_rng(4242)
+    for H, F, k in [(32, 25, 8), (72, 25, 16), (52, 5, 52), (256, 25, 3), (1, 1, 1)]:
+        B = 9
+        feat = g.random((B, H, F)).astype(np.float32)
+        lab = g.integers(0, k, size=(B, H)).astype(np.int32)       # arbitrary labels, some may be unused
+        sse = C.chai_cluster_error(dev(feat), dev(lab), k)
+        torch.cuda.synchronize()
+        assert np.array_equal(sse.cpu().numpy(), O.cluster_error(feat, lab, k)), (H, F, k)
+    # sweep on features of planted heads (cfg3 recipe): N samples = batch rows
+    cfg = W.CONFIGS["cfg3"].reduced(L=1, B=12, T=8)
+    planted = cfg.ks[0]
+    x = W.layer_inputs(cfg, 0)
+    feat = C.chai_score_features(dev(x.q5), dev(x.k), W.N_TOK, cfg.scale)
+    ks = [1, 2, 4, 8, 16, 32, 52]
+    curve, curve_o = [], []
+    feat_h = feat.cpu().numpy()
+    for k in ks:
+        init = W.distinct_heads(np.random.default_rng(k), cfg.B, cfg.H, k)
+        h2c, _, _, _ = C.chai_assign_clusters(feat, dev(init))
+        sse = C.chai_cluster_error(feat, h2c, k)
+        torch.cuda.synchronize()
+        h2c_o, _, _, _ = O.kmeans(feat_h, init)
+        assert np.array_equal(h2c.cpu().numpy(), h2c_o)
+        assert np.array_equal(sse.cpu().numpy(), O.cluster_error(feat_h, h2c_o, k))
+        curve.append(float(sse.mean()))
+        curve_o.append(float(O.cluster_error(feat_h, h2c_o, k).mean()))
+    picked = C.chai_pick_cluster_count(curve, ks, 0.05)
+    assert picked == O.pick_cluster_count(curve_o, ks, 0.05)
+    assert picked in (planted, 2 * planted) or picked == min(kk for kk in ks if kk >= planted)
+
+
 # ----------------------------------------------------------------------------------------------
 # cache kernels
 # ----------------------------------------------------------------------------------------------
