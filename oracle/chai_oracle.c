@@ -162,6 +162,76 @@ int chai_oracle_clustered_decode(const void *q, const void *k_full, const void *
 }
 
 /*
+ * Clustered-head attention over a block of prompt positions (Section 3.5: once
+ * membership is fixed, "we substitute MHA with Clustered Head Attention" for
+ * the rest of the request, i.e. also for the remaining prompt tokens whose
+ * cost the time-to-first-token figure of Section 4.4 includes; attention
+ * definition of Section 2 with the causal mask of a decoder-only model).
+ *
+ * Query row i (i = 0..Tq-1) sits at sequence position q_start + i and sees the
+ * keys and values of positions 0 .. q_start + i:
+ *   for cluster j with representative r:
+ *       s[t]   = scale * q[b][r][i] . K[b][r][t]          t <= q_start + i
+ *       p_j,i  = softmax(s)
+ *   for head h in cluster c:
+ *       out[b][h][i][:] = sum_t p_c,i[t] * V[b][h][t][:]
+ *
+ * q [B,H,Tq,d]; k_full, v [B,H,T_cap,d] (positions 0 .. q_start+Tq-1 valid);
+ * out [B,H,Tq,d] double.
+ */
+int chai_oracle_clustered_prefill(const void *q, const void *k_full, const void *v,
+                                  const int32_t *head_to_cluster, const int32_t *rep_heads,
+                                  int B, int H, int k, int Tq, int q_start, int T_cap, int d, int dtype,
+                                  double scale, double *out)
+{
+    if (!q || !k_full || !v || !head_to_cluster || !rep_heads || !out) return 1;
+    if (B < 0 || H < 1 || k < 1 || k > H || Tq < 1 || q_start < 0 || q_start + Tq > T_cap || d < 1) return 2;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return 3;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            int c = head_to_cluster[(int64_t)b * H + h];
+            if (c < 0 || c >= k) return 2;
+            int r = rep_heads[(int64_t)b * k + c];
+            if (r < 0 || r >= H) return 2;
+        }
+
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        for (int i = 0; i < Tq; ++i) {
+            const int n = q_start + i + 1;               /* keys this row sees */
+            double *s = (double *)malloc(sizeof(double) * (size_t)n);
+            double *p = (double *)malloc(sizeof(double) * (size_t)n * (size_t)k);
+            for (int j = 0; j < k; ++j) {
+                int r = rep_heads[(int64_t)b * k + j];
+                if (r < 0 || r >= H) continue;
+                int64_t qoff = (((int64_t)b * H + r) * Tq + i) * d;
+                int64_t koff = ((int64_t)b * H + r) * (int64_t)T_cap * d;
+                for (int t = 0; t < n; ++t) {
+                    double acc = 0.0;
+                    for (int c = 0; c < d; ++c)
+                        acc += load_elem(q, qoff + c, dtype) * load_elem(k_full, koff + (int64_t)t * d + c, dtype);
+                    s[t] = scale * acc;
+                }
+                softmax_row(s, n, p + (size_t)j * n);
+            }
+            for (int h = 0; h < H; ++h) {
+                const double *pc = p + (size_t)head_to_cluster[(int64_t)b * H + h] * n;
+                int64_t voff = ((int64_t)b * H + h) * (int64_t)T_cap * d;
+                double *o = out + (((int64_t)b * H + h) * Tq + i) * d;
+                for (int c = 0; c < d; ++c) {
+                    double acc = 0.0;
+                    for (int t = 0; t < n; ++t) acc += pc[t] * load_elem(v, voff + (int64_t)t * d + c, dtype);
+                    o[c] = acc;
+                }
+            }
+            free(s);
+            free(p);
+        }
+    }
+    return 0;
+}
+
+/*
  * Dense multi-head decode attention, the textbook definition of Section 2:
  * every head h uses its own q, K and V.
  *   out[b][h][:] = softmax_t(scale * q[b][h] . K[b][h][t]) applied to V[b][h]

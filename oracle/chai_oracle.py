@@ -38,6 +38,7 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     ci, cd = ctypes.c_int, ctypes.c_double
     L.chai_oracle_num_threads.restype = ci
     L.chai_oracle_clustered_decode.argtypes = [vp, vp, vp, i32p, i32p, ci, ci, ci, ci, ci, ci, ci, cd, vp, vp]
+    L.chai_oracle_clustered_prefill.argtypes = [vp, vp, vp, i32p, i32p, ci, ci, ci, ci, ci, ci, ci, ci, cd, vp]
     L.chai_oracle_dense_decode.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cd, vp, vp]
     L.chai_oracle_score_features.argtypes = [vp, vp, ci, ci, ci, ci, ci, i64, i64, cd, vp]
     L.chai_oracle_kmeans.argtypes = [vp, ci, ci, ci, ci, i32p, ci, i32p, i32p, i32p, i32p, vp]
@@ -118,6 +119,23 @@ def clustered_decode(q, k_full, v, head_to_cluster, rep_heads, T, scale, want_pr
                                             _f32(scale), _p(out), _p(probs))
     _check(rc, "clustered_decode")
     return (out, probs) if want_probs else out
+
+
+def clustered_prefill(q, k_full, v, head_to_cluster, rep_heads, q_start, scale):
+    """q [B,H,Tq,d] (rows at positions q_start..q_start+Tq-1); k_full, v [B,H,T_cap,d].  out [B,H,Tq,d] f64."""
+    q, k_full, v = _c(q), _c(k_full), _c(v)
+    dt = _dtype_code(q)
+    assert _dtype_code(k_full) == dt and _dtype_code(v) == dt
+    B, H, Tq, d = q.shape
+    T_cap = k_full.shape[2]
+    h2c = _c(head_to_cluster, np.int32)
+    rep = _c(rep_heads, np.int32)
+    k = rep.shape[1]
+    out = np.empty((B, H, Tq, d), np.float64)
+    rc = lib().chai_oracle_clustered_prefill(_p(q), _p(k_full), _p(v), _p(h2c), _p(rep), B, H, k, Tq, int(q_start),
+                                             T_cap, d, dt, _f32(scale), _p(out))
+    _check(rc, "clustered_prefill")
+    return out
 
 
 def dense_decode(q, k_cache, v, T, scale, want_probs=False):

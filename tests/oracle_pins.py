@@ -232,6 +232,34 @@ def pin_clustered_ignores_pruned_qk():
     assert np.allclose(out_p, out[:, perm], rtol=1e-13, atol=1e-14)
 
 
+def pin_prefill_matches_library_and_decode():
+    for seed, dt in [(71, W.F32), (72, W.BF16)]:
+        B, H, Tq, q_start, T_cap, d, kk = 2, 6, 9, 5, 16, 32, 3
+        g = np.random.default_rng(seed)
+        q = W.normal(g, (B, H, Tq, d), dt)
+        k = W.normal(g, (B, H, T_cap, d), dt)
+        v = W.normal(g, (B, H, T_cap, d), dt)
+        nan = np.nan if dt == W.F32 else 0x7FC0
+        k[:, :, q_start + Tq:], v[:, :, q_start + Tq:] = nan, nan           # never read
+        h2c, rep = W.random_membership(g, B, H, kk)
+        scale = float(np.float32(1.0 / math.sqrt(d)))
+        out = O.clustered_prefill(q, k, v, h2c, rep, q_start, scale)
+        # library statement: causal mask + scipy softmax + einsum, probabilities of the representative
+        T = q_start + Tq
+        s = scale * np.einsum("bhid,bhtd->bhit", W.as_f64(q), W.as_f64(k)[:, :, :T])
+        mask = np.arange(T)[None, :] <= (q_start + np.arange(Tq))[:, None]
+        p = scipy.special.softmax(np.where(mask, s, -np.inf), axis=-1)
+        ref = np.empty_like(out)
+        for b in range(B):
+            for h in range(H):
+                ref[b, h] = p[b, rep[b, h2c[b, h]]] @ W.as_f64(v)[b, h, :T]
+        assert np.allclose(out, ref, rtol=1e-12, atol=1e-13)
+        # row i of the block is the decode step at context q_start + i + 1
+        for i in (0, 4, Tq - 1):
+            dec = O.clustered_decode(np.ascontiguousarray(q[:, :, i]), k, v, h2c, rep, q_start + i + 1, scale)
+            assert np.array_equal(out[:, :, i], dec)
+
+
 # ----------------------------------------------------------------------------------------------
 # feature pins
 # ----------------------------------------------------------------------------------------------

@@ -24,7 +24,9 @@ SRC = os.path.join(os.path.dirname(O.__file__), "chai_oracle.c")
 MUTANTS = [
     ("clustered_scale_dropped", "s[t] = scale * acc;", "s[t] = acc;", 0,
      ["pin_clustered_matches_library"]),
-    ("dense_scale_dropped", "s[t] = scale * acc;", "s[t] = acc;", 1,
+    ("prefill_scale_dropped", "s[t] = scale * acc;", "s[t] = acc;", 1,
+     ["pin_prefill_matches_library_and_decode"]),
+    ("dense_scale_dropped", "s[t] = scale * acc;", "s[t] = acc;", 2,
      ["pin_dense_matches_library"]),
     ("clustered_keys_of_cluster_id_instead_of_representative",
      "int64_t koff = ((int64_t)b * H + r) * (int64_t)T_cap * d;", "int64_t koff = ((int64_t)b * H + j) * (int64_t)T_cap * d;", 0,
@@ -68,6 +70,12 @@ MUTANTS = [
      ["pin_cluster_error_and_count"]),
     ("cluster_count_returns_index", "{ *k_out = ks[i]; return 0; }", "{ *k_out = i; return 0; }", 0,
      ["pin_cluster_error_and_count"]),
+    ("prefill_sees_one_key_too_few", "const int n = q_start + i + 1;               /* keys this row sees */",
+     "const int n = q_start + i > 0 ? q_start + i : 1;", 0, ["pin_prefill_matches_library_and_decode"]),
+    ("prefill_not_causal", "const int n = q_start + i + 1;               /* keys this row sees */",
+     "const int n = q_start + Tq;", 0, ["pin_prefill_matches_library_and_decode"]),
+    ("prefill_query_row_stride", "int64_t qoff = (((int64_t)b * H + r) * Tq + i) * d;",
+     "int64_t qoff = (((int64_t)b * H + r) * Tq + (Tq - 1 - i)) * d;", 0, ["pin_prefill_matches_library_and_decode"]),
     ("compaction_source_stride", "int64_t src = ((int64_t)b * H + r) * T_cap + t;", "int64_t src = ((int64_t)b * H + r) * Tc_cap + t;", 0,
      ["pin_compaction_is_a_gather"]),
     ("compaction_copies_cluster_id_head", "int64_t src = ((int64_t)b * H + r) * T_cap + t;", "int64_t src = ((int64_t)b * H + j) * T_cap + t;", 0,
