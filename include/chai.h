@@ -259,6 +259,43 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
                                 int T, int T_cap, int d, int dtype, float scale, float *out,
                                 void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Clustered-head attention over a block of prompt positions: the prefill that
+ * follows the membership decision (Section 3.5: after the cluster membership
+ * is fixed, multi-head attention is replaced by clustered-head attention for
+ * the rest of the request; Section 4.4 prices it in the time to first token;
+ * attention definition of Section 2, causal).
+ *
+ * Query row i (0 <= i < Tq) sits at sequence position q_start + i and sees
+ * positions 0 .. q_start + i:
+ *   for cluster j with representative r = rep_heads[b][j] >= 0
+ *       p_j,i = softmax_t( scale * q[b][r][i] . k_compact[b][j][t] ),  t <= q_start + i
+ *   for head h in cluster c:  out[b][h][i][:] = sum_t p_c,i[t] * v_cache[b][h][t][:]
+ * The scores of a cluster are computed once and applied to the values of its
+ * member heads.  bf16 inputs only (CHAI_F32: CHAI_ERR_UNSUPPORTED).  Scores
+ * accumulate in fp32 from exact bf16 products; probabilities are rounded to
+ * fp16 and values widened exactly to fp16 for the second product (fp32
+ * accumulation), so |v| must not exceed 65504.
+ *
+ *   q         [B,H,Tq,d]        only representatives' rows are read
+ *   k_compact [B,k,Tc_cap,d]    keys of positions 0 .. q_start+Tq-1 present
+ *   v_cache   [B,H,T_cap,d]     values of positions 0 .. q_start+Tq-1 present
+ *   out       [B,H,Tq,d] fp32, written for heads whose cluster slot is in use
+ *   workspace chai_prefill_workspace_bytes(B,H,k) bytes, 256-byte aligned
+ * q_start + Tq <= min(T_cap, Tc_cap), Tq >= 1, q_start >= 0, H <= 4096.
+ *
+ * chai_dense_prefill_attention: the dense baseline (every head its own
+ * cluster, K read in place), same kernel.
+ */
+size_t chai_prefill_workspace_bytes(int B, int H, int k);
+int chai_prefill_attention(const void *q, const void *k_compact, const void *v_cache,
+                           const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k,
+                           int Tq, int q_start, int Tc_cap, int T_cap, int d, int dtype, float scale,
+                           float *out, void *workspace, size_t workspace_bytes, void *stream);
+int chai_dense_prefill_attention(const void *q, const void *k_cache, const void *v_cache, int B, int H, int Tq,
+                                 int q_start, int T_cap, int d, int dtype, float scale, float *out,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -21,6 +21,7 @@ SOURCES = {
     "api.hip": [],
     "decode.hip": [],
     "cache.hip": [],
+    "prefill.hip": [],
     # bit-exact k-means: no fused multiply-add, no reassociation
     "kmeans.hip": ["-ffp-contract=off", "-fno-fast-math"],
 }

@@ -1,0 +1,127 @@
+"""GPU parity of the clustered prefill attention (matrix-core kernel) against the CPU oracle."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+if not torch.cuda.is_available():
+    pytest.skip("needs a GPU", allow_module_level=True)
+
+import paper_2403_08058_amd as C
+import workloads as W
+from oracle import chai_oracle as O
+
+import gpu_util as G
+from gpu_util import dev
+
+# Probabilities are rounded to fp16 (11 significant bits) before the second product, everything else is exact
+# bf16 products with fp32 accumulation: errors of ~2^-12 per term average out to a few 1e-4 per row, inside the
+# 2e-3 contract for bf16 inputs.
+RTOL_PREFILL = 2e-3
+
+
+def run_case(B, H, kk, Tq, q_start, T_cap, seed, membership="random", sizes=None):
+    g = np.random.default_rng(seed)
+    q = W.normal(g, (B, H, Tq, 128), W.BF16)
+    k = W.normal(g, (B, H, T_cap, 128), W.BF16)
+    v = W.normal(g, (B, H, T_cap, 128), W.BF16)
+    nan = np.uint16(0x7FC0)
+    k[:, :, q_start + Tq:], v[:, :, q_start + Tq:] = nan, nan          # positions past the block are never read
+    if membership == "sized":
+        h2c, rep = W.sized_membership(g, B, H, sizes)
+    else:
+        h2c, rep = W.random_membership(g, B, H, kk)
+    scale = float(np.float32(1 / math.sqrt(128)))
+    kd, vd, qd, hd, rd = dev(k), dev(v), dev(q), dev(h2c), dev(rep)
+    kc = torch.zeros((B, kk, T_cap, 128), dtype=torch.bfloat16, device="cuda")
+    C.chai_compact_kcache(kd, rd, kc, q_start + Tq)
+    whole, out = G.guarded((B, H, Tq, 128), torch.float32, float("nan"))
+    ws = torch.full((max(C.chai_prefill_workspace_bytes(B, H, kk), 256),), 0xFF, dtype=torch.uint8, device="cuda")
+    C.chai_prefill_attention(qd, kc, vd, hd, rd, q_start, scale, out, ws)
+    torch.cuda.synchronize()
+    ref = O.clustered_prefill(q, k, v, h2c, rep, q_start, scale)
+    ok, worst = G.rows_close(out.cpu().numpy(), ref, RTOL_PREFILL)
+    assert ok, f"prefill off: worst err/allowed {worst:.3g}"
+    assert G.guards_intact(whole, (B, H, Tq, 128), float("nan"))
+    return worst, (q, k, v, qd, kd, vd)
+
+
+@pytest.mark.parametrize("B,H,kk,Tq,q_start,T_cap", [
+    (2, 8, 3, 200, 5, 256),        # ragged last query tile, odd group sizes
+    (1, 32, 8, 300, 5, 305),       # LLaMa-7B head structure, cache exactly full
+    (1, 32, 32, 130, 0, 160),      # every head alone, block starts at position 0
+    (2, 52, 4, 64, 100, 200),      # block in the middle of the sequence
+    (1, 72, 16, 1, 40, 64),        # a single query row
+    (1, 4, 1, 129, 31, 192),       # one cluster for all heads
+])
+def test_prefill_matches_oracle(B, H, kk, Tq, q_start, T_cap):
+    worst, _ = run_case(B, H, kk, Tq, q_start, T_cap, seed=B * 31 + H * 7 + Tq)
+    print(f"worst err/allowed = {worst:.3f}")
+
+
+def test_prefill_skewed_clusters():
+    run_case(2, 32, 4, 260, 5, 272, seed=5, membership="sized", sizes=(20, 6, 4, 2))
+
+
+def test_dense_prefill_and_one_head_per_cluster():
+    B, H, Tq, q_start, T_cap = 1, 8, 190, 5, 200
+    worst, (q, k, v, qd, kd, vd) = run_case(B, H, H, Tq, q_start, T_cap, seed=9)
+    scale = float(np.float32(1 / math.sqrt(128)))
+    out = torch.empty((B, H, Tq, 128), dtype=torch.float32, device="cuda")
+    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, H), 256),), dtype=torch.uint8, device="cuda")
+    C.chai_dense_prefill_attention(qd, kd, vd, q_start, scale, out, ws)
+    torch.cuda.synchronize()
+    ident = np.tile(np.arange(H, dtype=np.int32), (B, 1))
+    ref = O.clustered_prefill(q, k, v, ident, ident, q_start, scale)
+    ok, worst = G.rows_close(out.cpu().numpy(), ref, RTOL_PREFILL)
+    assert ok, worst
+
+
+def test_prefill_rows_equal_decode_steps():
+    """Row i of the prefill block is what the decode kernels give at context q_start + i + 1 (to fp16 rounding)."""
+    B, H, kk, Tq, q_start, T_cap = 1, 32, 8, 140, 5, 160
+    g = np.random.default_rng(77)
+    q = W.normal(g, (B, H, Tq, 128), W.BF16)
+    k = W.normal(g, (B, H, T_cap, 128), W.BF16)
+    v = W.normal(g, (B, H, T_cap, 128), W.BF16)
+    h2c, rep = W.random_membership(g, B, H, kk)
+    qd, kd, vd, hd, rd = dev(q), dev(k), dev(v), dev(h2c), dev(rep)
+    kc = torch.zeros((B, kk, T_cap, 128), dtype=torch.bfloat16, device="cuda")
+    C.chai_compact_kcache(kd, rd, kc, q_start + Tq)
+    out = torch.empty((B, H, Tq, 128), dtype=torch.float32, device="cuda")
+    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, kk), 256),), dtype=torch.uint8, device="cuda")
+    C.chai_prefill_attention(qd, kc, vd, hd, rd, q_start, 0.0884, out, ws)
+    dws = C.alloc_workspace(B, H, kk, T_cap, 128, C.CHAI_BF16)
+    for i in (0, 63, 139):
+        o = torch.empty((B, H, 128), dtype=torch.float32, device="cuda")
+        C.chai_decode_attention(qd[:, :, i].contiguous(), kc, vd, hd, rd, q_start + i + 1, 0.0884, o, dws)
+        torch.cuda.synchronize()
+        ok, worst = G.rows_close(out[:, :, i].cpu().numpy(), o.cpu().numpy().astype(np.float64), RTOL_PREFILL)
+        assert ok, (i, worst)
+
+
+def test_prefill_argument_errors():
+    B, H, kk, Tq = 1, 8, 2, 16
+    q = torch.zeros((B, H, Tq, 128), dtype=torch.bfloat16, device="cuda")
+    kc = torch.zeros((B, kk, 32, 128), dtype=torch.bfloat16, device="cuda")
+    v = torch.zeros((B, H, 32, 128), dtype=torch.bfloat16, device="cuda")
+    h2c = torch.zeros((B, H), dtype=torch.int32, device="cuda")
+    rep = torch.zeros((B, kk), dtype=torch.int32, device="cuda")
+    out = torch.zeros((B, H, Tq, 128), dtype=torch.float32, device="cuda")
+    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, kk), 256),), dtype=torch.uint8, device="cuda")
+
+    def status(*a):
+        with pytest.raises(C.ChaiError) as e:
+            C.chai_prefill_attention(*a)
+        return e.value.status
+
+    assert status(q, kc, v, h2c, rep, 17, 0.1, out, ws) == 2              # block runs past the cache
+    assert status(q, kc, v, h2c, rep, -1, 0.1, out, ws) == 2
+    assert status(q, kc, v, h2c, rep, 0, 0.1, out, ws[:64]) == 4
+    qf = torch.zeros((B, H, Tq, 128), dtype=torch.float32, device="cuda")
+    kf = torch.zeros((B, kk, 32, 128), dtype=torch.float32, device="cuda")
+    vf = torch.zeros((B, H, 32, 128), dtype=torch.float32, device="cuda")
+    assert status(qf, kf, vf, h2c, rep, 0, 0.1, out, ws) == 5              # fp32 inputs not supported here
