@@ -281,13 +281,15 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
  *   k_compact [B,k,Tc_cap,d]    keys of positions 0 .. q_start+Tq-1 present
  *   v_cache   [B,H,T_cap,d]     values of positions 0 .. q_start+Tq-1 present
  *   out       [B,H,Tq,d] fp32, written for heads whose cluster slot is in use
- *   workspace chai_prefill_workspace_bytes(B,H,k) bytes, 256-byte aligned
+ *   workspace chai_prefill_workspace_bytes(B,H,k,q_start+Tq) bytes, 256-byte
+ *             aligned (holds the work list and a transposed fp16 copy of the
+ *             values, B*H*d*roundup(q_start+Tq,64)*2 bytes)
  * q_start + Tq <= min(T_cap, Tc_cap), Tq >= 1, q_start >= 0, H <= 4096.
  *
  * chai_dense_prefill_attention: the dense baseline (every head its own
  * cluster, K read in place), same kernel.
  */
-size_t chai_prefill_workspace_bytes(int B, int H, int k);
+size_t chai_prefill_workspace_bytes(int B, int H, int k, int n_keys);
 int chai_prefill_attention(const void *q, const void *k_compact, const void *v_cache,
                            const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k,
                            int Tq, int q_start, int Tc_cap, int T_cap, int d, int dtype, float scale,

@@ -60,7 +60,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_decode_scores_timed.argtypes = L.chai_decode_scores.argtypes + [vp, vp]
     L.chai_decode_values_timed.argtypes = L.chai_decode_values.argtypes + [vp, vp]
     L.chai_prefill_workspace_bytes.restype = sz
-    L.chai_prefill_workspace_bytes.argtypes = [ci, ci, ci]
+    L.chai_prefill_workspace_bytes.argtypes = [ci, ci, ci, ci]
     L.chai_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     L.chai_dense_prefill_attention.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     for fn in EXPORTS:
@@ -254,8 +254,9 @@ def chai_dense_decode_attention(q, k_cache, v_cache, T: int, scale: float, out, 
     return out
 
 
-def chai_prefill_workspace_bytes(B: int, H: int, k: int) -> int:
-    return int(_lib.chai_prefill_workspace_bytes(B, H, k))
+def chai_prefill_workspace_bytes(B: int, H: int, k: int, n_keys: int) -> int:
+    """n_keys = q_start + Tq, the number of cached positions the block sees."""
+    return int(_lib.chai_prefill_workspace_bytes(B, H, k, n_keys))
 
 
 def chai_prefill_attention(q, k_compact, v_cache, head_to_cluster, rep_heads, q_start: int, scale: float, out,

@@ -240,10 +240,10 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
                                     true, KernelEvents(), s));
 }
 
-size_t chai_prefill_workspace_bytes(int B, int H, int k)
+size_t chai_prefill_workspace_bytes(int B, int H, int k, int n_keys)
 {
-    if (B < 0 || H < 1 || k < 1 || k > H) return 0;
-    return prefill_workspace_bytes(B > 0 ? B : 1, H, k);
+    if (B < 0 || H < 1 || k < 1 || k > H || n_keys < 1) return 0;
+    return prefill_workspace_bytes(B > 0 ? B : 1, H, k, n_keys);
 }
 
 static int check_prefill(const void *q, const void *kc, const void *v, const float *out, int B, int H, int k, int Tq,
@@ -257,7 +257,7 @@ static int check_prefill(const void *q, const void *kc, const void *v, const flo
     if (d != kHeadDim || dtype != CHAI_BF16 || B > kMaxGridYZ || H > 4096) return CHAI_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(kc) || !aligned16(v) || !aligned16(out)) return CHAI_ERR_ALIGN;
     if (B > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
-                  workspace_bytes < prefill_workspace_bytes(B, H, k)))
+                  workspace_bytes < prefill_workspace_bytes(B, H, k, q_start + Tq)))
         return CHAI_ERR_WORKSPACE;
     return CHAI_OK;
 }

@@ -54,7 +54,7 @@ size_t cluster_error_lds_bytes(int H, int F, int k);
 int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *h2c, const int32_t *rep, int B,
                    int H, int k, int Tq, int q_start, int Tc_cap, int T_cap, float scale, float *out,
                    void *workspace, bool identity, hipStream_t stream);
-size_t prefill_workspace_bytes(int B, int H, int k);
+size_t prefill_workspace_bytes(int B, int H, int k, int n_keys);
 
 int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
                           int T_cap, int Tc_cap, int dtype, hipStream_t stream);

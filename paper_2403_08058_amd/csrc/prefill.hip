@@ -8,11 +8,14 @@
 // MFMA tiles (v_mfma_f32_32x32x16, wave64), lane l = (r = l % 32, hl = l / 32):
 //   A[32][16]: lane holds A[r][8*hl .. 8*hl+7]     B[16][32]: lane holds B[8*hl .. 8*hl+7][r]
 //   D[32][32]: lane holds D[(v/4)*8 + hl*4 + v%4][r] for v = 0..15
-// Scores are computed transposed, S^T = K_tile Q^T (bf16 inputs): a lane then owns ONE query column and 16 of
-// the 32 keys of the tile, so row maxima and sums are in-lane plus one exchange with lane l^32, and the tile of
+// Scores are computed transposed, S^T = K_tile Q^T (bf16 inputs): a lane then owns ONE query column and half of
+// the keys of the tile, so row maxima and sums are in-lane plus one exchange with lane l^32, and the tile of
 // probabilities is already in the B-operand layout of O^T += V^T P^T.  That second product runs in fp16 (P in
-// [0,1] keeps 11 bits instead of bf16's 8; V is widened exactly from bf16 while it is transposed into LDS, so
-// values must stay inside the fp16 range, |v| <= 65504).
+// [0,256] keeps 11 bits instead of bf16's 8).  Its A operand needs 8 keys of one value column per lane, which a
+// row-major V cache cannot deliver, so a first kernel writes V^T once per call: fp16 (exact from bf16 inside
+// the fp16 range, |v| <= 65504), [d][T] per head, keys permuted inside every group of 16 into the order the
+// probability registers have, zero beyond the last key.  The main kernel then stages K and V^T tiles in LDS with
+// plain 16-byte copies and feeds every MFMA operand with one ds_read_b128.
 #include "chai_internal.h"
 
 namespace chai {
@@ -22,9 +25,13 @@ namespace {
 constexpr int kGroup = 2;          // member heads that share one score tile inside a workgroup
 constexpr int kQWave = 32;         // query rows per wave
 constexpr int kPWaves = 4;         // waves per workgroup
+constexpr int kPBlock = kPWaves * 64;
 constexpr int kQTile = kQWave * kPWaves;   // 128 query rows per workgroup
-constexpr int kKTile = 32;         // keys per tile
-constexpr int kVtStride = 40;      // halves per row of the transposed V tile in LDS (32 + 8 of padding)
+constexpr int kKTile = 64;         // keys per tile
+constexpr int kKStride = kHeadDim + 8;     // halves per K row in LDS (272 B: rows land on different banks)
+constexpr int kVStride = kKTile + 8;       // halves per V^T row in LDS (144 B)
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kRescaleSlack = 8.0f;      // log2 units a tile may exceed the running maximum before a rescale
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -37,17 +44,44 @@ union Frag16 {            // 16 bytes seen as a raw load, bf16 x 8 or fp16 x 8
     f16x8 h;
 };
 
-// position inside a 32-key LDS row of key jj, so that lane half hl finds the 8 keys of MFMA step s that match
-// its probability registers (keys 16s + (e/4)*8 + hl*4 + e%4, e = 0..7) in 8 consecutive halves
-__device__ __forceinline__ int key_slot(int jj)
+// Position of key jj (0..15) inside its group of 16 in V^T: lane half hl of MFMA step s multiplies its
+// probability registers e = 0..7, which hold keys 16s + (e/4)*8 + hl*4 + e%4, with 8 consecutive halves.
+__device__ __forceinline__ int key_slot16(int r16) { return 8 * ((r16 & 7) >> 2) + 4 * (r16 >> 3) + (r16 & 3); }
+
+// ---------------------------------------------------------------------------------------------------------
+// V^T: vt[b][h][dd][16*(t/16) + key_slot16(t%16)] = fp16(V[b][h][t][dd]) for t < n_keys, 0 up to Tp.
+// grid (Tp/64, H, B), 256 threads; a 64 x 128 tile goes through LDS.
+// ---------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void vt_kernel(const char *__restrict__ v, int H, int T_cap, int n_keys, int Tp,
+                                                 _Float16 *__restrict__ vt)
 {
-    const int s = jj >> 4, r = jj & 15;
-    return 16 * s + 8 * ((r & 7) >> 2) + 4 * (r >> 3) + (r & 3);
+    __shared__ _Float16 tile[kHeadDim][kKTile + 2];
+    const int tid = threadIdx.x, t0 = blockIdx.x * kKTile, h = blockIdx.y, b = blockIdx.z;
+    const char *vhead = v + ((size_t)b * H + h) * (size_t)T_cap * (kHeadDim * 2);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int piece = tid + i * 256, jj = piece >> 4, c8 = piece & 15;       // key row, 8-column block
+        Frag16 x;
+        x.raw = u32x4{0u, 0u, 0u, 0u};
+        if (t0 + jj < n_keys) x.raw = *reinterpret_cast<const u32x4 *>(vhead + (size_t)(t0 + jj) * (kHeadDim * 2) + c8 * 16);
+        const int slot = 16 * (jj >> 4) + key_slot16(jj & 15);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tile[c8 * 8 + e][slot] = (_Float16)(float)x.bf[e];
+    }
+    __syncthreads();
+    _Float16 *dst = vt + ((size_t)b * H + h) * (size_t)kHeadDim * Tp + t0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int idx = tid + i * 256, dd = idx >> 4, c4 = idx & 15;              // 4 keys = 8 bytes per item
+        const unsigned int lo = *reinterpret_cast<const unsigned int *>(&tile[dd][c4 * 4]);
+        const unsigned int hi = *reinterpret_cast<const unsigned int *>(&tile[dd][c4 * 4 + 2]);
+        *reinterpret_cast<uint2 *>(dst + (size_t)dd * Tp + c4 * 4) = make_uint2(lo, hi);
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
 // Work list: the heads of every cluster, in ascending order, cut into groups of at most kGroup.  One thread
-// per batch row (H <= a few hundred).  groups[b][g] = {cluster, n, head_0 .. head_{kGroup-1}}.
+// per batch row (H <= a few thousand).  groups[b][g] = {cluster, n, head_0 .. head_{kGroup-1}}.
 // ---------------------------------------------------------------------------------------------------------
 __global__ void prefill_plan_kernel(const int32_t *__restrict__ h2c, const int32_t *__restrict__ rep, int H, int k,
                                     int max_groups, int32_t *__restrict__ groups, int32_t *__restrict__ n_groups)
@@ -61,8 +95,10 @@ __global__ void prefill_plan_kernel(const int32_t *__restrict__ h2c, const int32
         int n = 0;
         for (int h = 0; h < H; ++h) {
             if (h2c[(size_t)b * H + h] != j) continue;
-            if (n == 0 && ng < max_groups) { g[ng * (2 + kGroup)] = j; }
-            if (ng < max_groups) g[ng * (2 + kGroup) + 2 + n] = h;
+            if (ng < max_groups) {
+                if (n == 0) g[ng * (2 + kGroup)] = j;
+                g[ng * (2 + kGroup) + 2 + n] = h;
+            }
             if (++n == kGroup) {
                 if (ng < max_groups) g[ng * (2 + kGroup) + 1] = n;
                 ++ng;
@@ -82,15 +118,16 @@ __global__ void prefill_plan_kernel(const int32_t *__restrict__ h2c, const int32
 // (dense attention); the work list is not read.
 // ---------------------------------------------------------------------------------------------------------
 template <bool IDENT>
-__global__ __launch_bounds__(kPWaves * 64) void prefill_kernel(const char *__restrict__ q, const char *__restrict__ kc,
-                                                               const char *__restrict__ v,
-                                                               const int32_t *__restrict__ rep,
-                                                               const int32_t *__restrict__ groups,
-                                                               const int32_t *__restrict__ n_groups, int H, int k,
-                                                               int Tq, int q_start, int Tc_cap, int T_cap,
-                                                               int max_groups, float scale, float *__restrict__ out)
+__global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict__ q, const char *__restrict__ kc,
+                                                          const _Float16 *__restrict__ vt,
+                                                          const int32_t *__restrict__ rep,
+                                                          const int32_t *__restrict__ groups,
+                                                          const int32_t *__restrict__ n_groups, int H, int k, int Tq,
+                                                          int q_start, int Tc_cap, int Tp, int max_groups, float scale,
+                                                          float *__restrict__ out)
 {
-    __shared__ _Float16 vt[kGroup][kHeadDim][kVtStride];
+    __shared__ __attribute__((aligned(16))) __bf16 k_lds[kKTile][kKStride];
+    __shared__ __attribute__((aligned(16))) _Float16 v_lds[kGroup][kHeadDim][kVStride];
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 31, hl = lane >> 5;
@@ -99,13 +136,13 @@ __global__ __launch_bounds__(kPWaves * 64) void prefill_kernel(const char *__res
     int cluster, n_mem, heads[kGroup];
     if (IDENT) {
         if (gi >= H) return;
-        cluster = gi; n_mem = 1; heads[0] = gi;
+        cluster = gi; n_mem = 1;
 #pragma unroll
-        for (int g = 1; g < kGroup; ++g) heads[g] = gi;
+        for (int g = 0; g < kGroup; ++g) heads[g] = gi;
     } else {
         if (gi >= n_groups[b]) return;
         const int32_t *gr = groups + ((size_t)b * max_groups + gi) * (2 + kGroup);
-        cluster = gr[0];
+        cluster = min(max(gr[0], 0), k - 1);
         n_mem = min(max(gr[1], 1), kGroup);
 #pragma unroll
         for (int g = 0; g < kGroup; ++g) heads[g] = min(max(gr[2 + min(g, n_mem - 1)], 0), H - 1);
@@ -115,10 +152,12 @@ __global__ __launch_bounds__(kPWaves * 64) void prefill_kernel(const char *__res
     const int i0 = qt * kQTile + w * kQWave;                 // first query row of this wave (relative)
     const int my_i = i0 + r;                                 // this lane's query row
     const int q_abs = q_start + min(my_i, Tq - 1);           // its sequence position (clamped for padding rows)
+    const int wave_first = q_start + min(i0, Tq - 1);
     const int wave_last = q_start + min(i0 + kQWave - 1, Tq - 1);     // last position any lane of the wave sees
     const int wg_last = q_start + min(qt * kQTile + kQTile - 1, Tq - 1);
     const int n_tiles = wg_last / kKTile + 1;                // key tiles 0 .. n_tiles-1 cover positions <= wg_last
     const bool wave_active = i0 < Tq;
+    const int n_keys = q_start + Tq;                         // keys that exist (rows past them are never read)
 
     // query fragments (B operand of S^T = K Q^T): Q[my_i][16*ks + 8*hl .. +7]
     Frag16 qf[kHeadDim / 16];
@@ -127,7 +166,49 @@ __global__ __launch_bounds__(kPWaves * 64) void prefill_kernel(const char *__res
 #pragma unroll
         for (int ks = 0; ks < kHeadDim / 16; ++ks) qf[ks].raw = *reinterpret_cast<const u32x4 *>(qrow + ks * 32);
     }
-    const char *kbase = kc + ((size_t)b * k + cluster) * (size_t)Tc_cap * (kHeadDim * 2) + hl * 16;
+
+    // global -> LDS staging: K tile = 1024 pieces of 16 bytes (4 per thread), V^T tile of a head = 128 rows x 8
+    // pieces (4 per thread).  A tile is fetched into registers one iteration ahead of its use.
+    const char *ksrc = kc + ((size_t)b * k + cluster) * (size_t)Tc_cap * (kHeadDim * 2);
+    const _Float16 *vsrc[kGroup];
+#pragma unroll
+    for (int g = 0; g < kGroup; ++g) vsrc[g] = vt + ((size_t)b * H + heads[g]) * (size_t)kHeadDim * Tp;
+    u32x4 kreg[4], vreg[kGroup][4];
+    auto fetch = [&](int kt) {
+        const int key0 = kt * kKTile;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
+            kreg[i] = *reinterpret_cast<const u32x4 *>(ksrc + (size_t)min(key0 + row, n_keys - 1) * (kHeadDim * 2) + c * 16);
+        }
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g) {
+            if (g < n_mem) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
+                    vreg[g][i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + (size_t)dd * Tp + key0 + c * 8);
+                }
+            }
+        }
+    };
+    auto stage = [&]() {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
+            *reinterpret_cast<u32x4 *>(&k_lds[row][c * 8]) = kreg[i];
+        }
+#pragma unroll
+        for (int g = 0; g < kGroup; ++g) {
+            if (g < n_mem) {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
+                    *reinterpret_cast<u32x4 *>(&v_lds[g][dd][c * 8]) = vreg[g][i];
+                }
+            }
+        }
+    };
 
     f32x16 acc[kGroup][kHeadDim / 32];
 #pragma unroll
@@ -136,84 +217,86 @@ __global__ __launch_bounds__(kPWaves * 64) void prefill_kernel(const char *__res
         for (int blk = 0; blk < kHeadDim / 32; ++blk)
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[g][blk][e] = 0.f;
-    float m_run = -INFINITY, l_run = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;          // running maximum (log2 units) and denominator of this query
+    const float scale2 = scale * kLog2e;
 
+    fetch(0);
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int key0 = kt * kKTile;
-        __syncthreads();                        // everyone is done reading the previous V tile
-        // V tiles of the member heads -> LDS, transposed, widened to fp16.  512 pieces of 16 bytes per head.
-#pragma unroll
-        for (int g = 0; g < kGroup; ++g) {
-            if (g < n_mem) {
-                const char *vhead = v + ((size_t)b * H + heads[g]) * (size_t)T_cap * (kHeadDim * 2);
-#pragma unroll
-                for (int pp = 0; pp < 2; ++pp) {
-                    const int piece = tid + pp * 256, jj = piece >> 4, c8 = piece & 15;
-                    Frag16 x;
-                    x.raw = *reinterpret_cast<const u32x4 *>(vhead + (size_t)min(key0 + jj, wg_last) * (kHeadDim * 2) +
-                                                             c8 * 16);
-                    const int slot = key_slot(jj);
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) vt[g][c8 * 8 + e][slot] = (_Float16)(float)x.bf[e];
-                }
-            }
-        }
+        __syncthreads();                        // everyone is done reading the previous tile
+        stage();
         __syncthreads();
-        if (!wave_active || key0 > wave_last) continue;     // uniform per wave; barriers above are always reached
+        if (kt + 1 < n_tiles) fetch(kt + 1);    // in flight while this tile is computed
+        if (!wave_active || key0 > wave_last) continue;     // uniform per wave; the barriers are always reached
 
-        // S^T tile: 32 keys x 32 queries
-        f32x16 st;
+        // S^T tile: 64 keys x 32 queries, as two 32-key blocks
+        f32x16 st[2];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) st[e] = 0.f;
-        {
-            const char *krow = kbase + (size_t)min(key0 + r, wg_last) * (kHeadDim * 2);
+        for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) st[kb][e] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < kHeadDim / 16; ++ks) {
                 Frag16 kf;
-                kf.raw = *reinterpret_cast<const u32x4 *>(krow + ks * 32);
-                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st, 0, 0, 0);
+                kf.raw = *reinterpret_cast<const u32x4 *>(&k_lds[kb * 32 + r][ks * 16 + hl * 8]);
+                st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st[kb], 0, 0, 0);
             }
         }
-        // scale, causal mask, online softmax for this lane's query column
+        // log2-domain scores, causal mask (only tiles that reach past the wave's first query need it)
+        const bool diagonal = key0 + kKTile - 1 > wave_first;
         float mx = -INFINITY;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const int key = key0 + (e >> 2) * 8 + hl * 4 + (e & 3);
-            const float sv = key <= q_abs ? st[e] * scale : -INFINITY;
-            st[e] = sv;
-            mx = fmaxf(mx, sv);
-        }
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float sv = st[kb][e] * scale2;
+                if (diagonal) {
+                    const int key = key0 + kb * 32 + (e >> 2) * 8 + hl * 4 + (e & 3);
+                    sv = key <= q_abs ? sv : -INFINITY;
+                }
+                st[kb][e] = sv;
+                mx = fmaxf(mx, sv);
+            }
         mx = fmaxf(mx, __shfl_xor(mx, 32));
-        const float m_new = fmaxf(m_run, mx);               // finite: tile 0 always holds key 0 <= q_abs
-        const float alpha = __expf(m_run - m_new);
-        float rs = 0.f;
+        // online softmax with a lazy reference: the running maximum only moves when a tile exceeds it by more
+        // than kRescaleSlack, so most tiles skip the rescaling of the accumulators (p stays below 2^slack)
+        const bool need = mx > m_run + kRescaleSlack;
+        const float m_new = need ? mx : m_run;
+        const float alpha = need ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;      // exp2(-inf) = 0 at the start
+        if (__any(need)) {
+            l_run *= alpha;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            const float p = __expf(st[e] - m_new);
-            st[e] = p;
-            rs += p;
+            for (int g = 0; g < kGroup; ++g)
+                if (g < n_mem)
+#pragma unroll
+                    for (int blk = 0; blk < kHeadDim / 32; ++blk)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[g][blk][e] *= alpha;
         }
-        rs += __shfl_xor(rs, 32);
-        l_run = l_run * alpha + rs;
         m_run = m_new;
-        Frag16 pf[2];
+        float rs = 0.f;
+        Frag16 pf[4];
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[s].h[e] = (_Float16)st[8 * s + e];
+            for (int e = 0; e < 16; ++e) {
+                const float p = __builtin_amdgcn_exp2f(st[kb][e] - m_run);
+                rs += p;
+                pf[kb * 2 + (e >> 3)].h[e & 7] = (_Float16)p;
+            }
+        rs += __shfl_xor(rs, 32);
+        l_run += rs;
 
-        // O^T[d][query] = alpha * O^T + V^T P^T for every member head
+        // O^T[d][query] += V^T P^T for every member head
 #pragma unroll
         for (int g = 0; g < kGroup; ++g) {
             if (g < n_mem) {
 #pragma unroll
                 for (int blk = 0; blk < kHeadDim / 32; ++blk) {
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) acc[g][blk][e] *= alpha;
-#pragma unroll
-                    for (int s = 0; s < 2; ++s) {
+                    for (int s = 0; s < kKTile / 16; ++s) {
                         Frag16 vf;
-                        vf.raw = *reinterpret_cast<const u32x4 *>(&vt[g][blk * 32 + r][16 * s + 8 * hl]);
+                        vf.raw = *reinterpret_cast<const u32x4 *>(&v_lds[g][blk * 32 + r][16 * s + 8 * hl]);
                         acc[g][blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf.h, pf[s].h, acc[g][blk], 0, 0, 0);
                     }
                 }
@@ -240,37 +323,50 @@ __global__ __launch_bounds__(kPWaves * 64) void prefill_kernel(const char *__res
     }
 }
 
+size_t round256(size_t x) { return (x + 255) / 256 * 256; }
+
 }  // namespace
 
 int prefill_max_groups(int H, int k) { return (H + kGroup - 1) / kGroup + k; }
 
-size_t prefill_workspace_bytes(int B, int H, int k)
+// work list + group counts + V^T
+size_t prefill_workspace_bytes(int B, int H, int k, int n_keys)
 {
-    const size_t groups = (size_t)B * prefill_max_groups(H, k) * (2 + kGroup) * sizeof(int32_t);
-    return (groups + 255) / 256 * 256 + ((size_t)B * sizeof(int32_t) + 255) / 256 * 256;
+    const size_t Tp = ((size_t)n_keys + kKTile - 1) / kKTile * kKTile;
+    return round256((size_t)B * prefill_max_groups(H, k) * (2 + kGroup) * sizeof(int32_t)) +
+           round256((size_t)B * sizeof(int32_t)) + round256((size_t)B * H * kHeadDim * Tp * sizeof(_Float16));
 }
 
 int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *h2c, const int32_t *rep, int B, int H,
                    int k, int Tq, int q_start, int Tc_cap, int T_cap, float scale, float *out, void *workspace,
                    bool identity, hipStream_t stream)
 {
+    const int n_keys = q_start + Tq;
+    const int Tp = (n_keys + kKTile - 1) / kKTile * kKTile;
     const int max_groups = identity ? H : prefill_max_groups(H, k);
-    int32_t *groups = static_cast<int32_t *>(workspace);
-    const size_t goff = ((size_t)B * prefill_max_groups(H, k) * (2 + kGroup) * sizeof(int32_t) + 255) / 256 * 256;
-    int32_t *n_groups = reinterpret_cast<int32_t *>(static_cast<char *>(workspace) + goff);
+    char *ws = static_cast<char *>(workspace);
+    int32_t *groups = reinterpret_cast<int32_t *>(ws);
+    ws += round256((size_t)B * prefill_max_groups(H, k) * (2 + kGroup) * sizeof(int32_t));
+    int32_t *n_groups = reinterpret_cast<int32_t *>(ws);
+    ws += round256((size_t)B * sizeof(int32_t));
+    _Float16 *vt = reinterpret_cast<_Float16 *>(ws);
     const int n_qt = (Tq + kQTile - 1) / kQTile;
+
+    vt_kernel<<<dim3(Tp / kKTile, H, B), 256, 0, stream>>>(static_cast<const char *>(v), H, T_cap, n_keys, Tp, vt);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return (int)e;
     if (identity) {
-        prefill_kernel<true><<<dim3(n_qt, H, B), kPWaves * 64, 0, stream>>>(
-            static_cast<const char *>(q), static_cast<const char *>(kc), static_cast<const char *>(v), nullptr, nullptr,
-            nullptr, H, k, Tq, q_start, Tc_cap, T_cap, max_groups, scale, out);
+        prefill_kernel<true><<<dim3(n_qt, H, B), kPBlock, 0, stream>>>(
+            static_cast<const char *>(q), static_cast<const char *>(kc), vt, nullptr, nullptr, nullptr, H, k, Tq,
+            q_start, Tc_cap, Tp, max_groups, scale, out);
         return (int)hipGetLastError();
     }
     prefill_plan_kernel<<<dim3(B), 64, 0, stream>>>(h2c, rep, H, k, max_groups, groups, n_groups);
-    hipError_t e = hipGetLastError();
+    e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    prefill_kernel<false><<<dim3(n_qt, max_groups, B), kPWaves * 64, 0, stream>>>(
-        static_cast<const char *>(q), static_cast<const char *>(kc), static_cast<const char *>(v), rep, groups, n_groups,
-        H, k, Tq, q_start, Tc_cap, T_cap, max_groups, scale, out);
+    prefill_kernel<false><<<dim3(n_qt, max_groups, B), kPBlock, 0, stream>>>(
+        static_cast<const char *>(q), static_cast<const char *>(kc), vt, rep, groups, n_groups, H, k, Tq, q_start,
+        Tc_cap, Tp, max_groups, scale, out);
     return (int)hipGetLastError();
 }
 

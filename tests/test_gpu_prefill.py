@@ -39,7 +39,7 @@ def run_case(B, H, kk, Tq, q_start, T_cap, seed, membership="random", sizes=None
     kc = torch.zeros((B, kk, T_cap, 128), dtype=torch.bfloat16, device="cuda")
     C.chai_compact_kcache(kd, rd, kc, q_start + Tq)
     whole, out = G.guarded((B, H, Tq, 128), torch.float32, float("nan"))
-    ws = torch.full((max(C.chai_prefill_workspace_bytes(B, H, kk), 256),), 0xFF, dtype=torch.uint8, device="cuda")
+    ws = torch.full((max(C.chai_prefill_workspace_bytes(B, H, kk, q_start + Tq), 256),), 0xFF, dtype=torch.uint8, device="cuda")
     C.chai_prefill_attention(qd, kc, vd, hd, rd, q_start, scale, out, ws)
     torch.cuda.synchronize()
     ref = O.clustered_prefill(q, k, v, h2c, rep, q_start, scale)
@@ -71,7 +71,7 @@ def test_dense_prefill_and_one_head_per_cluster():
     worst, (q, k, v, qd, kd, vd) = run_case(B, H, H, Tq, q_start, T_cap, seed=9)
     scale = float(np.float32(1 / math.sqrt(128)))
     out = torch.empty((B, H, Tq, 128), dtype=torch.float32, device="cuda")
-    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, H), 256),), dtype=torch.uint8, device="cuda")
+    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, H, q_start + Tq), 256),), dtype=torch.uint8, device="cuda")
     C.chai_dense_prefill_attention(qd, kd, vd, q_start, scale, out, ws)
     torch.cuda.synchronize()
     ident = np.tile(np.arange(H, dtype=np.int32), (B, 1))
@@ -92,7 +92,7 @@ def test_prefill_rows_equal_decode_steps():
     kc = torch.zeros((B, kk, T_cap, 128), dtype=torch.bfloat16, device="cuda")
     C.chai_compact_kcache(kd, rd, kc, q_start + Tq)
     out = torch.empty((B, H, Tq, 128), dtype=torch.float32, device="cuda")
-    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, kk), 256),), dtype=torch.uint8, device="cuda")
+    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, kk, q_start + Tq), 256),), dtype=torch.uint8, device="cuda")
     C.chai_prefill_attention(qd, kc, vd, hd, rd, q_start, 0.0884, out, ws)
     dws = C.alloc_workspace(B, H, kk, T_cap, 128, C.CHAI_BF16)
     for i in (0, 63, 139):
@@ -111,7 +111,7 @@ def test_prefill_argument_errors():
     h2c = torch.zeros((B, H), dtype=torch.int32, device="cuda")
     rep = torch.zeros((B, kk), dtype=torch.int32, device="cuda")
     out = torch.zeros((B, H, Tq, 128), dtype=torch.float32, device="cuda")
-    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, kk), 256),), dtype=torch.uint8, device="cuda")
+    ws = torch.empty((max(C.chai_prefill_workspace_bytes(B, H, kk, 32), 256),), dtype=torch.uint8, device="cuda")
 
     def status(*a):
         with pytest.raises(C.ChaiError) as e:
