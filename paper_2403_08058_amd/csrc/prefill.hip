@@ -24,10 +24,11 @@ namespace {
 
 constexpr int kGroup = 2;          // member heads that share one score tile inside a workgroup
 constexpr int kQWave = 32;         // query rows per wave
-constexpr int kPWaves = 4;         // waves per workgroup
+constexpr int kPWaves = 8;         // waves per workgroup (two per SIMD: one's MFMAs overlap the other's VALU work)
 constexpr int kPBlock = kPWaves * 64;
-constexpr int kQTile = kQWave * kPWaves;   // 128 query rows per workgroup
+constexpr int kQTile = kQWave * kPWaves;   // 256 query rows per workgroup
 constexpr int kKTile = 64;         // keys per tile
+constexpr int kStagePieces = kKTile * kHeadDim * 2 / 16 / kPBlock;   // 16-byte pieces of one tile per thread
 constexpr int kKStride = kHeadDim + 8;     // halves per K row in LDS (272 B: rows land on different banks)
 constexpr int kVStride = kKTile + 8;       // halves per V^T row in LDS (144 B)
 constexpr float kLog2e = 1.4426950408889634f;
@@ -114,7 +115,7 @@ __global__ void prefill_plan_kernel(const int32_t *__restrict__ h2c, const int32
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// grid (query tiles [largest first], max_groups, B), 256 threads.  IDENT: every head is its own cluster
+// grid (query tiles [largest first], max_groups, B), 512 threads.  IDENT: every head is its own cluster
 // (dense attention); the work list is not read.
 // ---------------------------------------------------------------------------------------------------------
 template <bool IDENT>
@@ -167,17 +168,17 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         for (int ks = 0; ks < kHeadDim / 16; ++ks) qf[ks].raw = *reinterpret_cast<const u32x4 *>(qrow + ks * 32);
     }
 
-    // global -> LDS staging: K tile = 1024 pieces of 16 bytes (4 per thread), V^T tile of a head = 128 rows x 8
-    // pieces (4 per thread).  A tile is fetched into registers one iteration ahead of its use.
+    // global -> LDS staging: K tile = 1024 pieces of 16 bytes, V^T tile of a head = 128 rows x 8
+    // pieces (kStagePieces per thread each).  A tile is fetched into registers one iteration ahead of its use.
     const char *ksrc = kc + ((size_t)b * k + cluster) * (size_t)Tc_cap * (kHeadDim * 2);
     const _Float16 *vsrc[kGroup];
 #pragma unroll
     for (int g = 0; g < kGroup; ++g) vsrc[g] = vt + ((size_t)b * H + heads[g]) * (size_t)kHeadDim * Tp;
-    u32x4 kreg[4], vreg[kGroup][4];
+    u32x4 kreg[kStagePieces], vreg[kGroup][kStagePieces];
     auto fetch = [&](int kt) {
         const int key0 = kt * kKTile;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
             kreg[i] = *reinterpret_cast<const u32x4 *>(ksrc + (size_t)min(key0 + row, n_keys - 1) * (kHeadDim * 2) + c * 16);
         }
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         for (int g = 0; g < kGroup; ++g) {
             if (g < n_mem) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < kStagePieces; ++i) {
                     const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
                     vreg[g][i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + (size_t)dd * Tp + key0 + c * 8);
                 }
@@ -194,7 +195,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     };
     auto stage = [&]() {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+        for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
             *reinterpret_cast<u32x4 *>(&k_lds[row][c * 8]) = kreg[i];
         }
@@ -202,7 +203,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         for (int g = 0; g < kGroup; ++g) {
             if (g < n_mem) {
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+                for (int i = 0; i < kStagePieces; ++i) {
                     const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
                     *reinterpret_cast<u32x4 *>(&v_lds[g][dd][c * 8]) = vreg[g][i];
                 }
@@ -242,21 +243,22 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
                 st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st[kb], 0, 0, 0);
             }
         }
-        // log2-domain scores, causal mask (only tiles that reach past the wave's first query need it)
+        // causal mask (only tiles that reach past the wave's first query need it) and the maximum of the raw
+        // scores; the scale (times log2 e) is folded into the exponent: p = exp2(s * scale2 - m)
         const bool diagonal = key0 + kKTile - 1 > wave_first;
-        float mx = -INFINITY;
+        const float neg = scale2 >= 0.f ? -INFINITY : INFINITY;      // raw value that scales to -inf
+        float ext = neg;                                              // max of raw scores (min if scale < 0)
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                float sv = st[kb][e] * scale2;
                 if (diagonal) {
                     const int key = key0 + kb * 32 + (e >> 2) * 8 + hl * 4 + (e & 3);
-                    sv = key <= q_abs ? sv : -INFINITY;
+                    st[kb][e] = key <= q_abs ? st[kb][e] : neg;
                 }
-                st[kb][e] = sv;
-                mx = fmaxf(mx, sv);
+                ext = scale2 >= 0.f ? fmaxf(ext, st[kb][e]) : fminf(ext, st[kb][e]);
             }
+        float mx = ext * scale2;
         mx = fmaxf(mx, __shfl_xor(mx, 32));
         // online softmax with a lazy reference: the running maximum only moves when a tile exceeds it by more
         // than kRescaleSlack, so most tiles skip the rescaling of the accumulators (p stays below 2^slack)
@@ -280,7 +282,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(st[kb][e] - m_run);
+                const float p = __builtin_amdgcn_exp2f(fmaf(st[kb][e], scale2, -m_run));
                 rs += p;
                 pf[kb * 2 + (e >> 3)].h[e & 7] = (_Float16)p;
             }
