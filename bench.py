@@ -32,6 +32,8 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--context", type=int, default=0, help="override the number of cached tokens (cfg4: 640 or 2048)")
+    ap.add_argument("--mode", default="decode", choices=["decode", "prefill"],
+                    help="decode (default, the headline metric) or the clustered prefill attention")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-phase-timing", action="store_true")
@@ -219,6 +221,100 @@ def cpu_baseline(cfg, layers, W, torch):
             "ms_per_step": step_s * 1e3, "parity_worst_normwise_err": worst}
 
 
+def prefill_main(args, cfg, torch, C, W):
+    """Clustered prefill attention (the block of prompt positions after the membership decision) of all layers of
+    the configuration: one step = B prompts of cfg.T tokens through every layer's attention.  Four layers' tensors
+    are resident and visited in turn (their working set is far beyond the caches)."""
+    import numpy as np
+    B, H, d, T = cfg.B, cfg.H, cfg.d, cfg.T
+    q_start = W.N_TOK
+    Tq = T - q_start
+    n_res = min(cfg.L, 4)
+    layers = []
+    for l in range(n_res):
+        k = cfg.ks[(l * cfg.L) // n_res if cfg.L > n_res else l]
+        seed = cfg.seed * 7919 + l
+        L = Layer()
+        L.k = k
+        g = W.rng(cfg.seed, l, "member")
+        if cfg.membership == "skewed":
+            h2c, rep = W.sized_membership(g, B, H, cfg.sizes)
+        else:
+            h2c, rep = W.random_membership(g, B, H, k)
+        L.h2c, L.rep = W.host_to_torch(h2c), W.host_to_torch(rep)
+        L.q = W.device_normal((B, H, Tq, d), cfg.dtype, seed + 1)
+        L.kfull = W.device_normal((B, H, T, d), cfg.dtype, seed + 2)
+        L.v = W.device_normal((B, H, T, d), cfg.dtype, seed + 3)
+        L.kc = torch.empty((B, k, T, d), dtype=torch.bfloat16, device="cuda")
+        C.chai_compact_kcache(L.kfull, L.rep, L.kc, T)
+        L.out = torch.empty((B, H, Tq, d), dtype=torch.float32, device="cuda")
+        layers.append(L)
+    ws = torch.empty((C.chai_prefill_workspace_bytes(B, H, H, T),), dtype=torch.uint8, device="cuda")
+    ks_all = [layers[(l * n_res) // cfg.L].k for l in range(cfg.L)]
+
+    def clustered_step():
+        for l in range(cfg.L):
+            L = layers[(l * n_res) // cfg.L]
+            C.chai_prefill_attention(L.q, L.kc, L.v, L.h2c, L.rep, q_start, cfg.scale, L.out, ws)
+
+    def dense_step():
+        for l in range(cfg.L):
+            L = layers[(l * n_res) // cfg.L]
+            C.chai_dense_prefill_attention(L.q, L.kfull, L.v, q_start, cfg.scale, L.out, ws)
+
+    steps, warmup = max(args.steps // 4, 2), max(args.warmup // 2, 1)
+    dense_ms = None
+    if not args.no_dense:
+        dense_ms, _ = timed_steps(dense_step, max(steps // 2, 1), warmup, torch)
+    ms, wall_ms = timed_steps(clustered_step, steps, warmup, torch)
+    pairs = sum(q_start + i + 1 for i in range(Tq))                      # (query, key) pairs under the causal mask
+    flops = sum(2 * d * pairs * B * (k + H) for k in ks_all)             # one score + one value product per pair
+    dense_flops = 2 * d * pairs * B * 2 * H * cfg.L
+    ach = flops / (ms * 1e-3) / 1e12
+    result = {
+        "metric": "clustered prefill attention prompt tokens/s (attention of all layers) + useful TFLOP/s vs MFMA peak",
+        "value": B * Tq / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name} prefill: {cfg.L} layers x {H} heads x d{d}, batch {B}, prompt {T} "
+                               f"(positions {q_start}..{T - 1} after the membership decision), clusters/layer "
+                               f"{sorted(set(ks_all))}, membership drawn ({cfg.membership if cfg.membership == 'skewed' else 'uniform'}), "
+                               f"{n_res} layers resident and visited in turn",
+                   "layers": cfg.L, "heads": H, "head_dim": d, "batch": B, "prompt": T},
+        "roofline": {"bound": "mfma", "kernel": "prefill_kernel (+ V^T pre-pass and work list, whole call)",
+                     "achieved": ach, "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0, "traffic": None,
+                     "flops_per_step": flops},
+        "host_wall_ms_per_step": wall_ms,
+    }
+    if dense_ms is not None:
+        result["dense_mha"] = {"ms_per_step": dense_ms, "TFLOPs": dense_flops / (dense_ms * 1e-3) / 1e12,
+                               "speedup_clustered_over_dense": dense_ms / ms,
+                               "ideal_speedup_by_flops": dense_flops / flops}
+    if not args.no_cpu_baseline:
+        from oracle import chai_oracle as O
+        L = layers[-1]
+        rows = 48
+        qs = T - rows
+        h2c, rep = L.h2c[:1].cpu().numpy(), L.rep[:1].cpu().numpy()
+        qh = W.torch_to_host_bits(L.q[:1, :, Tq - rows:])
+        kh, vh = W.torch_to_host_bits(L.kfull[:1]), W.torch_to_host_bits(L.v[:1])
+        clustered_step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        ref = O.clustered_prefill(qh, kh, vh, h2c, rep, qs, cfg.scale)
+        dt = time.perf_counter() - t0
+        got = L.out[:1, :, Tq - rows:].cpu().numpy().astype(np.float64)
+        err = float((np.abs(got - ref).max(-1) / np.abs(ref).max(-1)).max())
+        pairs_s = sum(qs + i + 1 for i in range(rows)) * (L.k + H)
+        step_s = dt * sum(pairs * B * (k + H) for k in ks_all) / pairs_s
+        result["cpu_baseline"] = {"value": B * Tq / step_s, "unit": "tokens/s", "cores": O.num_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"last {rows} query rows of batch row 0 of one layer ({dt:.2f} s of oracle time), "
+                                            f"scaled by (query, key, head) count to all rows, batch rows and layers (extrapolated)",
+                                  "parity_worst_normwise_err": err}
+    print(json.dumps(result))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -241,6 +337,9 @@ def main():
     if args.context:
         cfg = dataclasses.replace(cfg, T=args.context, T_cap=max(cfg.T_cap, args.context))
     B, H, d, T = cfg.B, cfg.H, cfg.d, cfg.T
+    if args.mode == "prefill":
+        prefill_main(args, cfg, torch, C, W)
+        return
 
     layers, t_member = build_layers(cfg, W, C, torch, keep_full_k=not args.no_dense)
     kmax = max(cfg.ks)

@@ -230,76 +230,76 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         if (kt + 1 < n_tiles) fetch(kt + 1);    // in flight while this tile is computed
         if (!wave_active || key0 > wave_last) continue;     // uniform per wave; the barriers are always reached
 
-        // S^T tile: 64 keys x 32 queries, as two 32-key blocks
-        f32x16 st[2];
+        // The staged tile is consumed as two halves of 32 keys, each: scores -> softmax update -> values, so only
+        // one 32 x 32 score block and its probabilities are live at a time.
+        const float neg = scale2 >= 0.f ? -INFINITY : INFINITY;      // raw score that scales to -inf
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < kKTile / 32; ++kb) {
+            const int kbase = key0 + kb * 32;
+            if (kbase > wave_last) break;                            // uniform per wave
+            // S^T block: 32 keys x 32 queries
+            f32x16 st;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) st[kb][e] = 0.f;
+            for (int e = 0; e < 16; ++e) st[e] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < kHeadDim / 16; ++ks) {
                 Frag16 kf;
                 kf.raw = *reinterpret_cast<const u32x4 *>(&k_lds[kb * 32 + r][ks * 16 + hl * 8]);
-                st[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st[kb], 0, 0, 0);
+                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st, 0, 0, 0);
             }
-        }
-        // causal mask (only tiles that reach past the wave's first query need it) and the maximum of the raw
-        // scores; the scale (times log2 e) is folded into the exponent: p = exp2(s * scale2 - m)
-        const bool diagonal = key0 + kKTile - 1 > wave_first;
-        const float neg = scale2 >= 0.f ? -INFINITY : INFINITY;      // raw value that scales to -inf
-        float ext = neg;                                              // max of raw scores (min if scale < 0)
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+            // causal mask (only blocks that reach past the wave's first query need it) and the maximum of the
+            // raw scores; the scale (times log2 e) is folded into the exponent: p = exp2(s * scale2 - m)
+            const bool diagonal = kbase + 31 > wave_first;
+            float ext = neg;                                          // max of raw scores (min if scale < 0)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 if (diagonal) {
-                    const int key = key0 + kb * 32 + (e >> 2) * 8 + hl * 4 + (e & 3);
-                    st[kb][e] = key <= q_abs ? st[kb][e] : neg;
+                    const int key = kbase + (e >> 2) * 8 + hl * 4 + (e & 3);
+                    st[e] = key <= q_abs ? st[e] : neg;
                 }
-                ext = scale2 >= 0.f ? fmaxf(ext, st[kb][e]) : fminf(ext, st[kb][e]);
+                ext = scale2 >= 0.f ? fmaxf(ext, st[e]) : fminf(ext, st[e]);
             }
-        float mx = ext * scale2;
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
-        // online softmax with a lazy reference: the running maximum only moves when a tile exceeds it by more
-        // than kRescaleSlack, so most tiles skip the rescaling of the accumulators (p stays below 2^slack)
-        const bool need = mx > m_run + kRescaleSlack;
-        const float m_new = need ? mx : m_run;
-        const float alpha = need ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;      // exp2(-inf) = 0 at the start
-        if (__any(need)) {
-            l_run *= alpha;
+            float mx = ext * scale2;
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            // online softmax with a lazy reference: the running maximum only moves when a block exceeds it by
+            // more than kRescaleSlack, so most blocks skip the rescaling of the accumulators (p < 2^slack)
+            const bool need = mx > m_run + kRescaleSlack;
+            const float m_new = need ? mx : m_run;
+            const float alpha = need ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;   // exp2(-inf) = 0 at the start
+            if (__any(need)) {
+                l_run *= alpha;
 #pragma unroll
-            for (int g = 0; g < kGroup; ++g)
-                if (g < n_mem)
+                for (int g = 0; g < kGroup; ++g)
+                    if (g < n_mem)
 #pragma unroll
-                    for (int blk = 0; blk < kHeadDim / 32; ++blk)
+                        for (int blk = 0; blk < kHeadDim / 32; ++blk)
 #pragma unroll
-                        for (int e = 0; e < 16; ++e) acc[g][blk][e] *= alpha;
-        }
-        m_run = m_new;
-        float rs = 0.f;
-        Frag16 pf[4];
-#pragma unroll
-        for (int kb = 0; kb < 2; ++kb)
+                            for (int e = 0; e < 16; ++e) acc[g][blk][e] *= alpha;
+            }
+            m_run = m_new;
+            float rs = 0.f;
+            Frag16 pf[2];
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                const float p = __builtin_amdgcn_exp2f(fmaf(st[kb][e], scale2, -m_run));
+                const float p = __builtin_amdgcn_exp2f(fmaf(st[e], scale2, -m_run));
                 rs += p;
-                pf[kb * 2 + (e >> 3)].h[e & 7] = (_Float16)p;
+                pf[e >> 3].h[e & 7] = (_Float16)p;
             }
-        rs += __shfl_xor(rs, 32);
-        l_run += rs;
+            rs += __shfl_xor(rs, 32);
+            l_run += rs;
 
-        // O^T[d][query] += V^T P^T for every member head
+            // O^T[d][query] += V^T P^T for every member head
 #pragma unroll
-        for (int g = 0; g < kGroup; ++g) {
-            if (g < n_mem) {
+            for (int g = 0; g < kGroup; ++g) {
+                if (g < n_mem) {
 #pragma unroll
-                for (int blk = 0; blk < kHeadDim / 32; ++blk) {
+                    for (int blk = 0; blk < kHeadDim / 32; ++blk) {
 #pragma unroll
-                    for (int s = 0; s < kKTile / 16; ++s) {
-                        Frag16 vf;
-                        vf.raw = *reinterpret_cast<const u32x4 *>(&v_lds[g][blk * 32 + r][16 * s + 8 * hl]);
-                        acc[g][blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf.h, pf[s].h, acc[g][blk], 0, 0, 0);
+                        for (int s = 0; s < 2; ++s) {
+                            Frag16 vf;
+                            vf.raw = *reinterpret_cast<const u32x4 *>(&v_lds[g][blk * 32 + r][kb * 32 + 16 * s + 8 * hl]);
+                            acc[g][blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf.h, pf[s].h, acc[g][blk], 0, 0, 0);
+                        }
                     }
                 }
             }
