@@ -272,7 +272,8 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
  *       p_j,i = softmax_t( scale * q[b][r][i] . k_compact[b][j][t] ),  t <= q_start + i
  *   for head h in cluster c:  out[b][h][i][:] = sum_t p_c,i[t] * v_cache[b][h][t][:]
  * The scores of a cluster are computed once and applied to the values of its
- * member heads.  bf16 inputs only (CHAI_F32: CHAI_ERR_UNSUPPORTED).  Scores
+ * member heads.  bf16 inputs only and scale > 0 (otherwise
+ * CHAI_ERR_UNSUPPORTED).  Scores
  * accumulate in fp32 from exact bf16 products; probabilities are rounded to
  * fp16 and values widened exactly to fp16 for the second product (fp32
  * accumulation), so |v| must not exceed 65504.

@@ -247,14 +247,14 @@ size_t chai_prefill_workspace_bytes(int B, int H, int k, int n_keys)
 }
 
 static int check_prefill(const void *q, const void *kc, const void *v, const float *out, int B, int H, int k, int Tq,
-                         int q_start, int Tc_cap, int T_cap, int d, int dtype, const void *workspace,
+                         int q_start, int Tc_cap, int T_cap, int d, int dtype, float scale, const void *workspace,
                          size_t workspace_bytes)
 {
     if (!q || !kc || !v || !out) return CHAI_ERR_NULL;
     if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
     if (B < 0 || H < 1 || k < 1 || k > H || Tq < 1 || q_start < 0 || d < 1) return CHAI_ERR_SHAPE;
     if ((long long)q_start + Tq > T_cap || (long long)q_start + Tq > Tc_cap) return CHAI_ERR_SHAPE;
-    if (d != kHeadDim || dtype != CHAI_BF16 || B > kMaxGridYZ || H > 4096) return CHAI_ERR_UNSUPPORTED;
+    if (d != kHeadDim || dtype != CHAI_BF16 || B > kMaxGridYZ || H > 4096 || !(scale > 0.f)) return CHAI_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(kc) || !aligned16(v) || !aligned16(out)) return CHAI_ERR_ALIGN;
     if (B > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
                   workspace_bytes < prefill_workspace_bytes(B, H, k, q_start + Tq)))
@@ -268,7 +268,7 @@ int chai_prefill_attention(const void *q, const void *k_compact, const void *v_c
                            void *stream)
 {
     if (!head_to_cluster || !rep_heads) return CHAI_ERR_NULL;
-    const int st = check_prefill(q, k_compact, v_cache, out, B, H, k, Tq, q_start, Tc_cap, T_cap, d, dtype, workspace,
+    const int st = check_prefill(q, k_compact, v_cache, out, B, H, k, Tq, q_start, Tc_cap, T_cap, d, dtype, scale, workspace,
                                  workspace_bytes);
     if (st != CHAI_OK) return st;
     if (B == 0) return CHAI_OK;
@@ -280,7 +280,7 @@ int chai_dense_prefill_attention(const void *q, const void *k_cache, const void 
                                  int q_start, int T_cap, int d, int dtype, float scale, float *out, void *workspace,
                                  size_t workspace_bytes, void *stream)
 {
-    const int st = check_prefill(q, k_cache, v_cache, out, B, H, H, Tq, q_start, T_cap, T_cap, d, dtype, workspace,
+    const int st = check_prefill(q, k_cache, v_cache, out, B, H, H, Tq, q_start, T_cap, T_cap, d, dtype, scale, workspace,
                                  workspace_bytes);
     if (st != CHAI_OK) return st;
     if (B == 0) return CHAI_OK;

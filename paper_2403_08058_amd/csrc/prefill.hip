@@ -232,7 +232,6 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
 
         // The staged tile is consumed as two halves of 32 keys, each: scores -> softmax update -> values, so only
         // one 32 x 32 score block and its probabilities are live at a time.
-        const float neg = scale2 >= 0.f ? -INFINITY : INFINITY;      // raw score that scales to -inf
 #pragma unroll
         for (int kb = 0; kb < kKTile / 32; ++kb) {
             const int kbase = key0 + kb * 32;
@@ -247,18 +246,21 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
                 kf.raw = *reinterpret_cast<const u32x4 *>(&k_lds[kb * 32 + r][ks * 16 + hl * 8]);
                 st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st, 0, 0, 0);
             }
-            // causal mask (only blocks that reach past the wave's first query need it) and the maximum of the
-            // raw scores; the scale (times log2 e) is folded into the exponent: p = exp2(s * scale2 - m)
-            const bool diagonal = kbase + 31 > wave_first;
-            float ext = neg;                                          // max of raw scores (min if scale < 0)
+            // causal mask: only blocks that reach past the wave's first query need it (a real branch, uniform
+            // per wave -- the empty asm keeps the compiler from turning it into 32 selects on every block)
+            if (kbase + 31 > wave_first) {
+                asm volatile("" ::: "memory");
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                if (diagonal) {
+                for (int e = 0; e < 16; ++e) {
                     const int key = kbase + (e >> 2) * 8 + hl * 4 + (e & 3);
-                    st[e] = key <= q_abs ? st[e] : neg;
+                    st[e] = key <= q_abs ? st[e] : -INFINITY;
                 }
-                ext = scale2 >= 0.f ? fmaxf(ext, st[e]) : fminf(ext, st[e]);
             }
+            // maximum of the raw scores (scale > 0 is required); the scale, times log2 e, is folded into the
+            // exponent: p = exp2(s * scale2 - m)
+            float ext = st[0];
+#pragma unroll
+            for (int e = 1; e < 16; ++e) ext = fmaxf(ext, st[e]);
             float mx = ext * scale2;
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             // online softmax with a lazy reference: the running maximum only moves when a block exceeds it by
