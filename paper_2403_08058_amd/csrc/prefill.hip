@@ -81,37 +81,56 @@ __global__ __launch_bounds__(256) void vt_kernel(const char *__restrict__ v, int
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Work list: the heads of every cluster, in ascending order, cut into groups of at most kGroup.  One thread
-// per batch row (H <= a few thousand).  groups[b][g] = {cluster, n, head_0 .. head_{kGroup-1}}.
+// Work list: the heads of every cluster, in ascending order, cut into groups of at most kGroup.
+// groups[b][g] = {cluster, n, head_0 .. head_{kGroup-1}}; clusters in ascending order.  One workgroup per
+// batch row: the membership row is copied to LDS, thread j counts cluster j, thread h ranks head h among the
+// heads of its cluster, and every head writes its own slot.  Heads that name no live cluster are left out.
+// Dynamic LDS: (H + 2k) ints.
 // ---------------------------------------------------------------------------------------------------------
-__global__ void prefill_plan_kernel(const int32_t *__restrict__ h2c, const int32_t *__restrict__ rep, int H, int k,
-                                    int max_groups, int32_t *__restrict__ groups, int32_t *__restrict__ n_groups)
+__global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t *__restrict__ h2c,
+                                                           const int32_t *__restrict__ rep, int H, int k,
+                                                           int max_groups, int32_t *__restrict__ groups,
+                                                           int32_t *__restrict__ n_groups)
 {
-    const int b = blockIdx.x;
-    if (threadIdx.x != 0) return;
-    int32_t *g = groups + (size_t)b * max_groups * (2 + kGroup);
-    int ng = 0;
-    for (int j = 0; j < k; ++j) {
-        if (rep[(size_t)b * k + j] < 0) continue;
+    extern __shared__ int32_t plan_lds[];
+    int32_t *member = plan_lds, *count = plan_lds + H, *base = count + k;
+    const int b = blockIdx.x, tid = threadIdx.x;
+    for (int h = tid; h < H; h += blockDim.x) {
+        const int c = h2c[(size_t)b * H + h];
+        member[h] = (c >= 0 && c < k && rep[(size_t)b * k + c] >= 0) ? c : -1;
+    }
+    __syncthreads();
+    for (int j = tid; j < k; j += blockDim.x) {
         int n = 0;
-        for (int h = 0; h < H; ++h) {
-            if (h2c[(size_t)b * H + h] != j) continue;
-            if (ng < max_groups) {
-                if (n == 0) g[ng * (2 + kGroup)] = j;
-                g[ng * (2 + kGroup) + 2 + n] = h;
-            }
-            if (++n == kGroup) {
-                if (ng < max_groups) g[ng * (2 + kGroup) + 1] = n;
-                ++ng;
-                n = 0;
-            }
-        }
-        if (n > 0) {
-            if (ng < max_groups) g[ng * (2 + kGroup) + 1] = n;
-            ++ng;
+        for (int h = 0; h < H; ++h) n += member[h] == j;
+        count[j] = n;
+    }
+    __syncthreads();
+    for (int j = tid; j < k; j += blockDim.x) {
+        int first = 0;
+        for (int i = 0; i < j; ++i) first += (count[i] + kGroup - 1) / kGroup;
+        base[j] = first;
+        if (j == k - 1) {
+            const int ng = first + (count[j] + kGroup - 1) / kGroup;
+            n_groups[b] = ng < max_groups ? ng : max_groups;
         }
     }
-    n_groups[b] = ng < max_groups ? ng : max_groups;
+    __syncthreads();
+    int32_t *g = groups + (size_t)b * max_groups * (2 + kGroup);
+    for (int h = tid; h < H; h += blockDim.x) {
+        const int c = member[h];
+        if (c < 0) continue;
+        int rank = 0;
+        for (int i = 0; i < h; ++i) rank += member[i] == c;
+        const int gi = base[c] + rank / kGroup, slot = rank % kGroup;
+        if (gi >= max_groups) continue;
+        g[gi * (2 + kGroup) + 2 + slot] = h;
+        if (slot == 0) {
+            const int left = count[c] - rank;
+            g[gi * (2 + kGroup)] = c;
+            g[gi * (2 + kGroup) + 1] = left < kGroup ? left : kGroup;
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -365,7 +384,7 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
             q_start, Tc_cap, Tp, max_groups, scale, out);
         return (int)hipGetLastError();
     }
-    prefill_plan_kernel<<<dim3(B), 64, 0, stream>>>(h2c, rep, H, k, max_groups, groups, n_groups);
+    prefill_plan_kernel<<<dim3(B), 256, (size_t)(H + 2 * k) * sizeof(int32_t), stream>>>(h2c, rep, H, k, max_groups, groups, n_groups);
     e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
     prefill_kernel<false><<<dim3(n_qt, max_groups, B), kPBlock, 0, stream>>>(
