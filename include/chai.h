@@ -275,8 +275,9 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
  * member heads.  bf16 inputs only and scale > 0 (otherwise
  * CHAI_ERR_UNSUPPORTED).  Scores
  * accumulate in fp32 from exact bf16 products; probabilities are rounded to
- * fp16 and values widened exactly to fp16 for the second product (fp32
- * accumulation), so |v| must not exceed 65504.
+ * fp16 and values converted to fp16 for the second product (fp32
+ * accumulation): the conversion is exact for 2^-14 <= |v| <= 65504, loses
+ * low bits below that, and |v| must not exceed 65504.
  *
  *   q         [B,H,Tq,d]        only representatives' rows are read
  *   k_compact [B,k,Tc_cap,d]    keys of positions 0 .. q_start+Tq-1 present
@@ -289,12 +290,22 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
  *
  * chai_dense_prefill_attention: the dense baseline (every head its own
  * cluster, K read in place), same kernel.
+ *
+ * chai_prefill_attention_timed: the same call with two hipEvent_t handles
+ * passed as void* (timing enabled, either may be NULL) that the runtime
+ * stamps with the begin and the end of the main kernel; the V^T pre-pass and
+ * the work-list kernel that run before it are outside the pair.
  */
 size_t chai_prefill_workspace_bytes(int B, int H, int k, int n_keys);
 int chai_prefill_attention(const void *q, const void *k_compact, const void *v_cache,
                            const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k,
                            int Tq, int q_start, int Tc_cap, int T_cap, int d, int dtype, float scale,
                            float *out, void *workspace, size_t workspace_bytes, void *stream);
+int chai_prefill_attention_timed(const void *q, const void *k_compact, const void *v_cache,
+                                 const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k,
+                                 int Tq, int q_start, int Tc_cap, int T_cap, int d, int dtype, float scale,
+                                 float *out, void *workspace, size_t workspace_bytes, void *stream,
+                                 void *start_event, void *stop_event);
 int chai_dense_prefill_attention(const void *q, const void *k_cache, const void *v_cache, int B, int H, int Tq,
                                  int q_start, int T_cap, int d, int dtype, float scale, float *out,
                                  void *workspace, size_t workspace_bytes, void *stream);

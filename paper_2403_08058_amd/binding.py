@@ -26,7 +26,7 @@ EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_as
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention",
            "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
            "chai_dense_decode_attention", "chai_prefill_workspace_bytes", "chai_prefill_attention",
-           "chai_dense_prefill_attention"]
+           "chai_prefill_attention_timed", "chai_dense_prefill_attention"]
 
 
 class ChaiError(RuntimeError):
@@ -62,6 +62,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_prefill_workspace_bytes.restype = sz
     L.chai_prefill_workspace_bytes.argtypes = [ci, ci, ci, ci]
     L.chai_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
+    L.chai_prefill_attention_timed.argtypes = L.chai_prefill_attention.argtypes + [vp, vp]
     L.chai_dense_prefill_attention.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     for fn in EXPORTS:
         if fn not in ("chai_status_string", "chai_decode_workspace_bytes", "chai_prefill_workspace_bytes"):
@@ -259,9 +260,24 @@ def chai_prefill_workspace_bytes(B: int, H: int, k: int, n_keys: int) -> int:
     return int(_lib.chai_prefill_workspace_bytes(B, H, k, n_keys))
 
 
+def chai_prefill_attention_timed(q, k_compact, v_cache, head_to_cluster, rep_heads, q_start: int, scale: float, out,
+                                 workspace, stream=None, start_event=None, stop_event=None):
+    """q [B,H,Tq,d] (rows at positions q_start..), k_compact [B,k,Tc_cap,d], v_cache [B,H,T_cap,d] -> out [B,H,Tq,d] fp32.
+    start_event / stop_event: raw hipEvent_t handles (ints) stamped with the main kernel's begin and end, or None."""
+    B, H, Tq, d = q.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    T_cap = v_cache.shape[2]
+    _check("chai_prefill_attention_timed",
+           _lib.chai_prefill_attention_timed(_ptr(q), _ptr(k_compact), _ptr(v_cache), _ptr(head_to_cluster),
+                                             _ptr(rep_heads), B, H, k, Tq, q_start, Tc_cap, T_cap, d, dtype_code(q),
+                                             scale, _ptr(out), _ptr(workspace),
+                                             workspace.numel() * workspace.element_size(), _stream(stream),
+                                             start_event, stop_event))
+    return out
+
+
 def chai_prefill_attention(q, k_compact, v_cache, head_to_cluster, rep_heads, q_start: int, scale: float, out,
                            workspace, stream=None):
-    """q [B,H,Tq,d] (rows at positions q_start..), k_compact [B,k,Tc_cap,d], v_cache [B,H,T_cap,d] -> out [B,H,Tq,d] fp32."""
     B, H, Tq, d = q.shape
     k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
     T_cap = v_cache.shape[2]

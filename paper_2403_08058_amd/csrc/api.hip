@@ -262,18 +262,32 @@ static int check_prefill(const void *q, const void *kc, const void *v, const flo
     return CHAI_OK;
 }
 
-int chai_prefill_attention(const void *q, const void *k_compact, const void *v_cache, const int32_t *head_to_cluster,
-                           const int32_t *rep_heads, int B, int H, int k, int Tq, int q_start, int Tc_cap, int T_cap,
-                           int d, int dtype, float scale, float *out, void *workspace, size_t workspace_bytes,
-                           void *stream)
+int chai_prefill_attention_timed(const void *q, const void *k_compact, const void *v_cache,
+                                 const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k, int Tq,
+                                 int q_start, int Tc_cap, int T_cap, int d, int dtype, float scale, float *out,
+                                 void *workspace, size_t workspace_bytes, void *stream, void *start_event,
+                                 void *stop_event)
 {
     if (!head_to_cluster || !rep_heads) return CHAI_ERR_NULL;
     const int st = check_prefill(q, k_compact, v_cache, out, B, H, k, Tq, q_start, Tc_cap, T_cap, d, dtype, scale, workspace,
                                  workspace_bytes);
     if (st != CHAI_OK) return st;
     if (B == 0) return CHAI_OK;
+    KernelEvents ev;
+    ev.start = static_cast<hipEvent_t>(start_event);
+    ev.stop = static_cast<hipEvent_t>(stop_event);
     return hip_status(launch_prefill(q, k_compact, v_cache, head_to_cluster, rep_heads, B, H, k, Tq, q_start, Tc_cap,
-                                     T_cap, scale, out, workspace, false, static_cast<hipStream_t>(stream)));
+                                     T_cap, scale, out, workspace, false, ev, static_cast<hipStream_t>(stream)));
+}
+
+int chai_prefill_attention(const void *q, const void *k_compact, const void *v_cache, const int32_t *head_to_cluster,
+                           const int32_t *rep_heads, int B, int H, int k, int Tq, int q_start, int Tc_cap, int T_cap,
+                           int d, int dtype, float scale, float *out, void *workspace, size_t workspace_bytes,
+                           void *stream)
+{
+    return chai_prefill_attention_timed(q, k_compact, v_cache, head_to_cluster, rep_heads, B, H, k, Tq, q_start, Tc_cap,
+                                        T_cap, d, dtype, scale, out, workspace, workspace_bytes, stream, nullptr,
+                                        nullptr);
 }
 
 int chai_dense_prefill_attention(const void *q, const void *k_cache, const void *v_cache, int B, int H, int Tq,
@@ -285,7 +299,7 @@ int chai_dense_prefill_attention(const void *q, const void *k_cache, const void 
     if (st != CHAI_OK) return st;
     if (B == 0) return CHAI_OK;
     return hip_status(launch_prefill(q, k_cache, v_cache, nullptr, nullptr, B, H, H, Tq, q_start, T_cap, T_cap, scale,
-                                     out, workspace, true, static_cast<hipStream_t>(stream)));
+                                     out, workspace, true, KernelEvents{}, static_cast<hipStream_t>(stream)));
 }
 
 }  // extern "C"

@@ -50,10 +50,11 @@ int launch_cluster_error(const float *feat, const int32_t *h2c, int B, int H, in
                          hipStream_t stream);
 size_t cluster_error_lds_bytes(int H, int F, int k);
 
-// Clustered attention over a block of prompt positions (bf16 only).  identity = dense attention.
+// Clustered attention over a block of prompt positions (bf16 only).  identity = dense attention.  The events
+// cover the main kernel, not the V^T pre-pass or the work list.
 int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *h2c, const int32_t *rep, int B,
                    int H, int k, int Tq, int q_start, int Tc_cap, int T_cap, float scale, float *out,
-                   void *workspace, bool identity, hipStream_t stream);
+                   void *workspace, bool identity, const KernelEvents &ev, hipStream_t stream);
 size_t prefill_workspace_bytes(int B, int H, int k, int n_keys);
 
 int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,

@@ -18,6 +18,8 @@
 // plain 16-byte copies and feeds every MFMA operand with one ds_read_b128.
 #include "chai_internal.h"
 
+#include <hip/hip_ext.h>
+
 namespace chai {
 
 namespace {
@@ -362,7 +364,7 @@ size_t prefill_workspace_bytes(int B, int H, int k, int n_keys)
 
 int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *h2c, const int32_t *rep, int B, int H,
                    int k, int Tq, int q_start, int Tc_cap, int T_cap, float scale, float *out, void *workspace,
-                   bool identity, hipStream_t stream)
+                   bool identity, const KernelEvents &ev, hipStream_t stream)
 {
     const int n_keys = q_start + Tq;
     const int Tp = (n_keys + kKTile - 1) / kKTile * kKTile;
@@ -379,17 +381,20 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
     if (identity) {
-        prefill_kernel<true><<<dim3(n_qt, H, B), kPBlock, 0, stream>>>(
-            static_cast<const char *>(q), static_cast<const char *>(kc), vt, nullptr, nullptr, nullptr, H, k, Tq,
-            q_start, Tc_cap, Tp, max_groups, scale, out);
+        hipExtLaunchKernelGGL(prefill_kernel<true>, dim3(n_qt, H, B), dim3(kPBlock), 0, stream, ev.start, ev.stop, 0,
+                              static_cast<const char *>(q), static_cast<const char *>(kc),
+                              static_cast<const _Float16 *>(vt), static_cast<const int32_t *>(nullptr),
+                              static_cast<const int32_t *>(nullptr), static_cast<const int32_t *>(nullptr), H, k, Tq,
+                              q_start, Tc_cap, Tp, max_groups, scale, out);
         return (int)hipGetLastError();
     }
     prefill_plan_kernel<<<dim3(B), 256, (size_t)(H + 2 * k) * sizeof(int32_t), stream>>>(h2c, rep, H, k, max_groups, groups, n_groups);
     e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    prefill_kernel<false><<<dim3(n_qt, max_groups, B), kPBlock, 0, stream>>>(
-        static_cast<const char *>(q), static_cast<const char *>(kc), vt, rep, groups, n_groups, H, k, Tq, q_start,
-        Tc_cap, Tp, max_groups, scale, out);
+    hipExtLaunchKernelGGL(prefill_kernel<false>, dim3(n_qt, max_groups, B), dim3(kPBlock), 0, stream, ev.start, ev.stop,
+                          0, static_cast<const char *>(q), static_cast<const char *>(kc),
+                          static_cast<const _Float16 *>(vt), rep, static_cast<const int32_t *>(groups),
+                          static_cast<const int32_t *>(n_groups), H, k, Tq, q_start, Tc_cap, Tp, max_groups, scale, out);
     return (int)hipGetLastError();
 }
 

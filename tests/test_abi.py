@@ -24,7 +24,7 @@ def declared_functions():
 
 def test_header_symbols_exported(chai):
     names = declared_functions()
-    assert len(names) == 18 and "chai_assign_clusters" in names and "chai_compact_kcache" in names \
+    assert len(names) == 19 and "chai_assign_clusters" in names and "chai_compact_kcache" in names \
         and "chai_decode_attention" in names
     L = ctypes.CDLL(chai.LIB_PATH)
     for n in names:
@@ -80,6 +80,24 @@ def test_argument_checks_run_before_any_launch(chai):
     assert L.chai_assign_clusters(fake, 0, 32, 25, 8, fake, 50, fake, fake, fake, None, None) == 0  # B = 0: no-op
     assert L.chai_score_features(fake, fake, 1, 32, 9, 128, 1, 9 * 128, 9 * 128, 0.1, fake, None) == 5
     assert L.chai_score_features(fake, fake, 1, 32, 5, 128, 1, 4 * 128, 5 * 128, 0.1, fake, None) == 2
+    # prefill: positions [q_start, q_start + Tq) of a bf16 cache; scale must be positive
+    big = 1 << 34
+    pf = lambda **kw: L.chai_prefill_attention(*[kw.get(n, dflt) for n, dflt in (
+        ("q", fake), ("kc", fake), ("v", fake), ("h2c", fake), ("rep", fake), ("B", 1), ("H", 32), ("k", 8), ("Tq", 64),
+        ("q_start", 0), ("Tc_cap", 64), ("T_cap", 64), ("d", 128), ("dtype", 1), ("scale", 0.1), ("out", fake),
+        ("ws", 0x1000), ("ws_bytes", big), ("stream", None))])
+    assert pf(h2c=None) == 1
+    assert pf(Tq=65) == 2                       # runs past the cache
+    assert pf(q_start=1) == 2
+    assert pf(dtype=2) == 3
+    assert pf(ws_bytes=16) == 4
+    assert pf(dtype=0) == 5                     # fp32 prefill is not built
+    assert pf(scale=0.0) == 5 and pf(scale=-0.1) == 5 and pf(scale=float("nan")) == 5
+    assert pf(q=fake + 2) == 7
+    assert pf(B=0) == 0                         # empty batch: no-op
+    assert L.chai_dense_prefill_attention(fake, fake, fake, 1, 32, 64, 0, 64, 128, 1, -1.0, fake, 0x1000, big, None) == 5
+    assert chai.chai_prefill_workspace_bytes(4, 32, 8, 100) == chai.chai_prefill_workspace_bytes(4, 32, 8, 128)
+    assert chai.chai_prefill_workspace_bytes(4, 32, 8, 129) > chai.chai_prefill_workspace_bytes(4, 32, 8, 128)
 
 
 def test_pick_cluster_count_runs_on_the_host(chai):
