@@ -15,7 +15,9 @@
  * Parity pins (tests marked "not gpu"): library softmax/matmul on small
  * shapes, hand-worked examples, closed forms, the k = H and identical-Q/K
  * reductions to dense attention, brute-force k-means over all partitions,
- * an independent Lloyd implementation with the same start, index gathers.
+ * an independent Lloyd implementation with the same start, index gathers,
+ * the shared-value ablation against dense attention of the representative,
+ * the nearest-to-mean representative against hand-worked cases and numpy.
  * Unpinned: nothing in this file.  (How well clustered attention
  * approximates dense attention on trained models is not computed here at
  * all; it needs weights and datasets.)
@@ -162,10 +164,11 @@ int chai_oracle_clustered_decode(const void *q, const void *k_full, const void *
 }
 
 /*
- * Clustered-head attention over a block of prompt positions (Section 3.5: once
- * membership is fixed, "we substitute MHA with Clustered Head Attention" for
- * the rest of the request, i.e. also for the remaining prompt tokens whose
- * cost the time-to-first-token figure of Section 4.4 includes; attention
+ * Clustered-head attention over a block of prompt positions (Section 3.5 and
+ * its inference figure: once membership is fixed, clustered attention takes
+ * the place of multi-head attention for the rest of the request, i.e. also
+ * for the remaining prompt tokens whose cost the time-to-first-token figure
+ * of Section 4.4 includes; attention
  * definition of Section 2 with the causal mask of a decoder-only model).
  *
  * Query row i (i = 0..Tq-1) sits at sequence position q_start + i and sees the
@@ -279,6 +282,59 @@ int chai_oracle_dense_decode(const void *q, const void *k_cache, const void *v,
 }
 
 /*
+ * Ablation of Section 4.5 (pruning values as well): every head of a cluster
+ * also takes the VALUES of the representative, i.e. the whole head is
+ * replaced by the representative,
+ *     out[b][h][:] = sum_t p_c[t] * V[b][rep[b][c]][t][:],   c = cluster of h,
+ * with p_c as in chai_oracle_clustered_decode.  Layouts as there.
+ */
+int chai_oracle_shared_v_decode(const void *q, const void *k_full, const void *v,
+                                const int32_t *head_to_cluster, const int32_t *rep_heads,
+                                int B, int H, int k, int T, int T_cap, int d, int dtype,
+                                double scale, double *out)
+{
+    if (!q || !k_full || !v || !head_to_cluster || !rep_heads || !out) return 1;
+    if (B < 0 || H < 1 || k < 1 || k > H || T < 1 || T > T_cap || d < 1) return 2;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return 3;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            int c = head_to_cluster[(int64_t)b * H + h];
+            if (c < 0 || c >= k) return 2;
+            int r = rep_heads[(int64_t)b * k + c];
+            if (r < 0 || r >= H) return 2;
+        }
+
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            int r = rep_heads[(int64_t)b * k + head_to_cluster[(int64_t)b * H + h]];
+            double *s = (double *)malloc(sizeof(double) * (size_t)T);
+            double *p = (double *)malloc(sizeof(double) * (size_t)T);
+            int64_t qoff = ((int64_t)b * H + r) * d;
+            int64_t roff = ((int64_t)b * H + r) * (int64_t)T_cap * d;
+            for (int t = 0; t < T; ++t) {
+                double acc = 0.0;
+                for (int i = 0; i < d; ++i)
+                    acc += load_elem(q, qoff + i, dtype) *
+                           load_elem(k_full, roff + (int64_t)t * d + i, dtype);
+                s[t] = scale * acc;
+            }
+            softmax_row(s, T, p);
+            double *o = out + ((int64_t)b * H + h) * d;
+            for (int i = 0; i < d; ++i) {
+                double acc = 0.0;
+                for (int t = 0; t < T; ++t)
+                    acc += p[t] * load_elem(v, roff + (int64_t)t * d + i, dtype);
+                o[i] = acc;
+            }
+            free(s);
+            free(p);
+        }
+    }
+    return 0;
+}
+
+/*
  * Clustering features (Section 3.3: the attention scores a head produces on
  * the first few tokens of a request; Section 3.1 defines the compared
  * quantity as the softmax of Q K^T).  For every (b,h) the n_tok x n_tok
@@ -374,9 +430,53 @@ int chai_oracle_cluster_error(const float *feat, const int32_t *head_to_cluster,
 }
 
 /*
- * Number of clusters from the error curve (Section 3.2: "choose the number
- * of clusters when the error plateaus"; the paper reads the elbow plot by
- * eye).  Reading used here: with err[i] the mean clustering error at ks[i]
+ * Alternative choice of the head that stands for a cluster (the paper speaks
+ * of one representative head per cluster without fixing which one): the
+ * member whose features lie closest (squared Euclidean distance) to the mean
+ * of the cluster's members; equal distances -> the lowest head index.
+ * Empty cluster slots get -1.  rep_out [B,k].
+ */
+int chai_oracle_closest_representatives(const float *feat, const int32_t *head_to_cluster, int B, int H, int F,
+                                        int k, int32_t *rep_out)
+{
+    if (!feat || !head_to_cluster || !rep_out) return 1;
+    if (B < 0 || H < 1 || F < 1 || k < 1 || k > H) return 2;
+    double *mean = (double *)malloc(sizeof(double) * (size_t)F);
+    for (int b = 0; b < B; ++b) {
+        const float *X = feat + (int64_t)b * H * F;
+        const int32_t *lab = head_to_cluster + (int64_t)b * H;
+        for (int j = 0; j < k; ++j) {
+            int cnt = 0;
+            for (int h = 0; h < H; ++h)
+                if (lab[h] == j) ++cnt;
+            int best = -1;
+            double best_d = 0.0;
+            if (cnt > 0) {
+                for (int f = 0; f < F; ++f) {
+                    double acc = 0.0;
+                    for (int h = 0; h < H; ++h)
+                        if (lab[h] == j) acc = acc + (double)X[(int64_t)h * F + f];
+                    mean[f] = acc / (double)cnt;
+                }
+                for (int h = 0; h < H; ++h) {
+                    if (lab[h] != j) continue;
+                    double dist = sqdist(X + (int64_t)h * F, mean, F);
+                    if (best < 0 || dist < best_d) {
+                        best = h;
+                        best_d = dist;
+                    }
+                }
+            }
+            rep_out[(int64_t)b * k + j] = best;
+        }
+    }
+    free(mean);
+    return 0;
+}
+
+/*
+ * Number of clusters from the error curve (Section 3.2: the count is taken
+ * where the error curve flattens; the paper reads the elbow plot by eye).  Reading used here: with err[i] the mean clustering error at ks[i]
  * (ks ascending), pick the smallest ks[i] whose error has come down to
  * within a fraction `tol` of the whole drop,
  *     err[i] - err[n-1] <= tol * (err[0] - err[n-1]).

@@ -39,6 +39,8 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.chai_oracle_num_threads.restype = ci
     L.chai_oracle_clustered_decode.argtypes = [vp, vp, vp, i32p, i32p, ci, ci, ci, ci, ci, ci, ci, cd, vp, vp]
     L.chai_oracle_clustered_prefill.argtypes = [vp, vp, vp, i32p, i32p, ci, ci, ci, ci, ci, ci, ci, ci, cd, vp]
+    L.chai_oracle_shared_v_decode.argtypes = [vp, vp, vp, i32p, i32p, ci, ci, ci, ci, ci, ci, ci, cd, vp]
+    L.chai_oracle_closest_representatives.argtypes = [vp, i32p, ci, ci, ci, ci, i32p]
     L.chai_oracle_dense_decode.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cd, vp, vp]
     L.chai_oracle_score_features.argtypes = [vp, vp, ci, ci, ci, ci, ci, i64, i64, cd, vp]
     L.chai_oracle_kmeans.argtypes = [vp, ci, ci, ci, ci, i32p, ci, i32p, i32p, i32p, i32p, vp]
@@ -121,6 +123,25 @@ def clustered_decode(q, k_full, v, head_to_cluster, rep_heads, T, scale, want_pr
     return (out, probs) if want_probs else out
 
 
+def shared_v_decode(q, k_full, v, head_to_cluster, rep_heads, T, scale):
+    """As clustered_decode, but every head also takes the representative's values.  Returns out [B,H,d] f64."""
+    q, k_full, v = _c(q), _c(k_full), _c(v)
+    dt = _dtype_code(q)
+    assert _dtype_code(k_full) == dt and _dtype_code(v) == dt
+    B, H, d = q.shape
+    T_cap = k_full.shape[2]
+    assert k_full.shape == (B, H, T_cap, d) and v.shape == (B, H, T_cap, d)
+    h2c = _c(head_to_cluster, np.int32)
+    rep = _c(rep_heads, np.int32)
+    k = rep.shape[1]
+    assert h2c.shape == (B, H) and rep.shape == (B, k)
+    out = np.empty((B, H, d), np.float64)
+    rc = lib().chai_oracle_shared_v_decode(_p(q), _p(k_full), _p(v), _p(h2c), _p(rep), B, H, k, T, T_cap, d, dt,
+                                           _f32(scale), _p(out))
+    _check(rc, "shared_v_decode")
+    return out
+
+
 def clustered_prefill(q, k_full, v, head_to_cluster, rep_heads, q_start, scale):
     """q [B,H,Tq,d] (rows at positions q_start..q_start+Tq-1); k_full, v [B,H,T_cap,d].  out [B,H,Tq,d] f64."""
     q, k_full, v = _c(q), _c(k_full), _c(v)
@@ -194,6 +215,17 @@ def cluster_error(feat, head_to_cluster, k):
     sse = np.empty((B,), np.float64)
     _check(lib().chai_oracle_cluster_error(_p(feat), _p(h2c), B, H, F, int(k), _p(sse)), "cluster_error")
     return sse
+
+
+def closest_representatives(feat, head_to_cluster, k):
+    """Per cluster the member closest to the mean of the members (ties -> lowest head), -1 for empty slots; [B,k]."""
+    feat = _c(feat, np.float32)
+    h2c = _c(head_to_cluster, np.int32)
+    B, H, F = feat.shape
+    rep = np.empty((B, int(k)), np.int32)
+    _check(lib().chai_oracle_closest_representatives(_p(feat), _p(h2c), B, H, F, int(k), _p(rep)),
+           "closest_representatives")
+    return rep
 
 
 def pick_cluster_count(err, ks, tol):

@@ -232,6 +232,61 @@ def pin_clustered_ignores_pruned_qk():
     assert np.allclose(out_p, out[:, perm], rtol=1e-13, atol=1e-14)
 
 
+def pin_shared_v_takes_the_whole_representative():
+    # the ablation that prunes values too: every head's output is the dense attention output of its
+    # representative (library re-statement), whatever the pruned heads hold in Q, K and V
+    for seed, dt in [(61, W.F32), (62, W.BF16)]:
+        B, H, T, T_cap, d, kk = 2, 9, 21, 25, 32, 4
+        q, k, v = _rand_case(seed, B, H, T, T_cap, d, dt)
+        h2c, rep = W.random_membership(np.random.default_rng(seed), B, H, kk)
+        scale = float(np.float32(1.0 / math.sqrt(d)))
+        out = O.shared_v_decode(q, k, v, h2c, rep, T, scale)
+        ref, _ = lib_dense(q, k, v, T, scale)
+        for b in range(B):
+            for h in range(H):
+                assert np.allclose(out[b, h], ref[b, rep[b, h2c[b, h]]], rtol=1e-12, atol=1e-13)
+        own = O.clustered_decode(q, k, v, h2c, rep, T, scale)
+        for b in range(B):
+            for h in range(H):
+                same = np.allclose(out[b, h], own[b, h], rtol=1e-9, atol=1e-12)
+                assert same == (h in rep[b]), "only representatives agree with the variant that keeps every V"
+        q2, k2, v2 = q.copy(), k.copy(), v.copy()
+        for b in range(B):
+            for h in range(H):
+                if h not in rep[b]:
+                    for a in (q2, k2, v2):
+                        a[b, h] = 0x7FC0 if dt == W.BF16 else np.nan
+        assert np.array_equal(O.shared_v_decode(q2, k2, v2, h2c, rep, T, scale), out)
+
+
+def pin_closest_representatives():
+    for c in _golden("representative_worked.json")["cases"]:
+        X = np.asarray(c["feat"], np.float32)[None]
+        lab = np.asarray(c["labels"], np.int32)[None]
+        assert O.closest_representatives(X, lab, c["k"])[0].tolist() == c["rep"], c["how"]
+    # numpy re-statement on random partitions (distinct distances with probability 1)
+    g = np.random.default_rng(801)
+    B, H, F, kk = 5, 24, 25, 7
+    X = g.random((B, H, F)).astype(np.float32)
+    lab = g.integers(0, kk, size=(B, H)).astype(np.int32)
+    lab[0][lab[0] == 3] = 2                                    # an empty slot
+    rep = O.closest_representatives(X, lab, kk)
+    for b in range(B):
+        for j in range(kk):
+            members = np.nonzero(lab[b] == j)[0]
+            if len(members) == 0:
+                assert rep[b, j] == -1
+                continue
+            pts = X[b, members].astype(np.float64)
+            dist = ((pts - pts.mean(axis=0)) ** 2).sum(axis=1)
+            assert rep[b, j] == members[np.argmin(dist)]
+    # one head per cluster: every head represents itself; identical members: the lowest one
+    assert np.array_equal(O.closest_representatives(X, np.tile(np.arange(H, dtype=np.int32), (B, 1)), H),
+                          np.tile(np.arange(H, dtype=np.int32), (B, 1)))
+    same = np.repeat(X[:, :1], H, axis=1)
+    assert np.all(O.closest_representatives(same, np.zeros((B, H), np.int32), 1) == 0)
+
+
 def pin_prefill_matches_library_and_decode():
     for seed, dt in [(71, W.F32), (72, W.BF16)]:
         B, H, Tq, q_start, T_cap, d, kk = 2, 6, 9, 5, 16, 32, 3

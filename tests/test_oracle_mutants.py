@@ -70,6 +70,16 @@ MUTANTS = [
      ["pin_cluster_error_and_count"]),
     ("cluster_count_returns_index", "{ *k_out = ks[i]; return 0; }", "{ *k_out = i; return 0; }", 0,
      ["pin_cluster_error_and_count"]),
+    ("shared_v_keeps_own_values", "acc += p[t] * load_elem(v, roff + (int64_t)t * d + i, dtype);",
+     "acc += p[t] * load_elem(v, ((int64_t)b * H + h) * (int64_t)T_cap * d + (int64_t)t * d + i, dtype);", 0,
+     ["pin_shared_v_takes_the_whole_representative"]),
+    ("shared_v_scale_dropped", "s[t] = scale * acc;", "s[t] = acc;", 3, ["pin_shared_v_takes_the_whole_representative"]),
+    ("closest_representative_is_farthest", "if (best < 0 || dist < best_d) {", "if (best < 0 || dist > best_d) {", 0,
+     ["pin_closest_representatives"]),
+    ("closest_representative_ties_to_highest", "if (best < 0 || dist < best_d) {", "if (best < 0 || dist <= best_d) {", 0,
+     ["pin_closest_representatives"]),
+    ("closest_representative_mean_over_all_heads", "mean[f] = acc / (double)cnt;", "mean[f] = acc / (double)H;", 1,
+     ["pin_closest_representatives"]),
     ("prefill_sees_one_key_too_few", "const int n = q_start + i + 1;               /* keys this row sees */",
      "const int n = q_start + i > 0 ? q_start + i : 1;", 0, ["pin_prefill_matches_library_and_decode"]),
     ("prefill_not_causal", "const int n = q_start + i + 1;               /* keys this row sees */",
