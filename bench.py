@@ -32,8 +32,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--context", type=int, default=0, help="override the number of cached tokens (cfg4: 640 or 2048)")
-    ap.add_argument("--mode", default="decode", choices=["decode", "prefill"],
-                    help="decode (default, the headline metric) or the clustered prefill attention")
+    ap.add_argument("--mode", default="decode", choices=["decode", "prefill", "shared-v"],
+                    help="decode (default, the headline metric), the clustered prefill attention, or the decode "
+                         "ablation that prunes values as well")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-phase-timing", action="store_true")
@@ -353,6 +354,81 @@ def prefill_main(args, cfg, torch, C, W):
     print(json.dumps(result))
 
 
+def shared_v_main(args, cfg, torch, C, W):
+    """Decode step of the ablation that prunes values too (every head takes its representative's V): both caches
+    compact, k streams each.  Priced against the HBM roofline like the headline path, and against the method
+    proper (own V) on the same layers."""
+    import numpy as np
+    B, H, d, T, e = cfg.B, cfg.H, cfg.d, cfg.T, cfg.elem_bytes
+    layers, _ = build_layers(cfg, W, C, torch, keep_full_k=False)
+    vcs = []
+    for L in layers:
+        vc = torch.empty_like(L.kc)
+        C.chai_compact_kcache(L.v, L.rep, vc, T)
+        vcs.append(vc)
+    ws = C.alloc_workspace(B, H, max(cfg.ks), T, d, cfg.dtype)
+
+    def shared_step():
+        for L, vc in zip(layers, vcs):
+            C.chai_decode_attention_shared_v(L.q, L.kc, vc, L.h2c, L.rep, T, cfg.scale, L.out, ws)
+
+    def own_v_step():
+        for L in layers:
+            C.chai_decode_attention(L.q, L.kc, L.v, L.h2c, L.rep, T, cfg.scale, L.out, ws)
+
+    own_ms, _ = timed_steps(own_v_step, max(args.steps // 2, 3), args.warmup, torch)
+    ms, wall_ms = timed_steps(shared_step, args.steps, args.warmup, torch)
+    alg = sum(2 * B * L.k * T * d * e + B * L.k * d * e + 2 * B * H * 4 + B * H * d * 4 for L in layers)
+    ach = alg / (ms * 1e-3) / 1e9
+    result = {
+        "metric": "decode-attn tokens/s of the ablation with shared values + achieved HBM GB/s vs peak",
+        "value": B / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if cfg.dtype == W.BF16 else "f32", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}, values pruned as well: {cfg.L} layers x {H} heads x d{d}, batch {B}, "
+                               f"context {T}, clusters/layer {sorted(set(cfg.ks))}, membership {cfg.membership}",
+                   "layers": cfg.L, "heads": H, "head_dim": d, "batch": B, "context": T},
+        "roofline": {"bound": "hbm", "kernel": "whole call (score, value and member-combine kernels)",
+                     "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                     "traffic": None, "bytes_per_step": alg},
+        "host_wall_ms_per_step": wall_ms,
+        "own_values": {"ms_per_step": own_ms, "speedup_shared_over_own": own_ms / ms,
+                       "ideal_speedup_by_bytes": cfg.clustered_bytes_per_step() / alg},
+    }
+    if not args.no_cpu_baseline:
+        from oracle import chai_oracle as O
+        shared_step()
+        torch.cuda.synchronize()
+        n_s = min(len(layers), 16)
+        idx = sorted(set(int(round(i * (len(layers) - 1) / max(n_s - 1, 1))) for i in range(n_s)))
+        dt, err = 0.0, 0.0
+        for li in idx:
+            L, vc = layers[li], vcs[li]
+            rep, h2c = L.rep.cpu().numpy(), L.h2c.cpu().numpy()
+            # full caches for the oracle: it reads only the representatives' rows (pinned), the rest stays zero
+            kf = np.zeros((B, H, T, d), np.uint16 if cfg.dtype == W.BF16 else np.float32)
+            vf = np.zeros_like(kf)
+            kc_h, vc_h = W.torch_to_host_bits(L.kc[:, :, :T]), W.torch_to_host_bits(vc[:, :, :T])
+            for b in range(B):
+                for j in range(L.k):
+                    if rep[b, j] >= 0:
+                        kf[b, rep[b, j]], vf[b, rep[b, j]] = kc_h[b, j], vc_h[b, j]
+            qh = W.torch_to_host_bits(L.q)
+            t0 = time.perf_counter()
+            ref = O.shared_v_decode(qh, kf, vf, h2c, rep, T, cfg.scale)
+            dt += time.perf_counter() - t0
+            got = L.out.cpu().numpy().astype(np.float64)
+            err = max(err, float((np.abs(got - ref).max(-1) / np.abs(ref).max(-1)).max()))
+        dt /= len(idx)
+        result["cpu_baseline"] = {"value": B / (dt * cfg.L), "unit": "tokens/s", "cores": O.num_threads(),
+                                  "kind": "oracle",
+                                  "sample": f"every batch row of {len(idx)} of {cfg.L} layers ({dt * len(idx):.1f} s of "
+                                            f"oracle time; it attends per head, so its cost does not depend on "
+                                            f"the cluster count), scaled to all layers",
+                                  "parity_worst_normwise_err": err}
+    print(json.dumps(result))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -377,6 +453,9 @@ def main():
     B, H, d, T = cfg.B, cfg.H, cfg.d, cfg.T
     if args.mode == "prefill":
         prefill_main(args, cfg, torch, C, W)
+        return
+    if args.mode == "shared-v":
+        shared_v_main(args, cfg, torch, C, W)
         return
 
     layers, t_member = build_layers(cfg, W, C, torch, keep_full_k=not args.no_dense)

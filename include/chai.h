@@ -145,6 +145,23 @@ int chai_cluster_error(const float *feat, const int32_t *head_to_cluster, int B,
 int chai_pick_cluster_count(const double *mean_error, const int32_t *ks, int n, double tol, int32_t *k_out);
 
 /*
+ * Variant of the choice of representative.  Sections 3.4-3.5 and Fig. 3 let
+ * one head stand for its cluster without fixing which member; the default
+ * everywhere in this library is the lowest-numbered member (what
+ * chai_assign_clusters returns).  This call returns instead, for every
+ * cluster of a given partition, the member whose features lie nearest
+ * (squared Euclidean distance, fp64) to the mean of the cluster's members;
+ * equal distances -> the lowest head; unused labels -> -1.  Bit-identical to
+ * the sequential evaluation (means and distances as in chai_cluster_error).
+ *   feat [B,H,F] fp32; head_to_cluster [B,H] int32, labels in [0,k);
+ *   rep_heads [B,k] int32, written.  Limits as for chai_assign_clusters.
+ * The maps it returns can be passed to every other entry point (they accept
+ * any member as representative).
+ */
+int chai_closest_representatives(const float *feat, const int32_t *head_to_cluster, int B, int H, int F, int k,
+                                 int32_t *rep_heads, void *stream);
+
+/*
  * K-cache pruning (Section 3.5: once membership is fixed, the keys of the
  * pruned heads are removed; Section 4.3 / Fig. 3: all values are kept).
  *   k_compact[b][j][t][:] = k_full[b][rep_heads[b][j]][t][:]   for t < T.
@@ -245,6 +262,34 @@ int chai_decode_values_timed(const void *v_cache, const int32_t *head_to_cluster
                              int B, int H, int k, int T, int T_cap, int d, int dtype, float *out,
                              float *probs_out, void *workspace, size_t workspace_bytes, void *stream,
                              void *start_event, void *stop_event);
+
+/*
+ * Ablation of Section 4.5 (values pruned as well): every head of a cluster
+ * takes the representative's values too, so only the representatives' K and
+ * V are cached.  The paper reports that this costs accuracy; it is here to
+ * price the variant.
+ *   out[b][h][:] = sum_t p_c[t] * v_compact[b][c][t][:],  c = head_to_cluster[b][h]
+ * with p_c the probabilities of chai_decode_attention.
+ *
+ *   v_compact [B,k,Tv_cap,d]  slot j = values of head rep_heads[b][j]; build it
+ *                             with chai_compact_kcache (a plain gather that
+ *                             serves V as well) and grow it with
+ *                             chai_append_kv_shared_v
+ *   out       [B,H,d] fp32    rows of heads whose label is outside [0,k) are
+ *                             left untouched
+ *   workspace chai_decode_workspace_bytes(B,H,k,T,...) bytes suffice
+ * Other arguments, limits and errors as chai_decode_attention.
+ *
+ * chai_append_kv_shared_v: position `pos` of both compact caches takes the
+ * new token's K and V rows of the representatives (k_new, v_new [B,H,d]).
+ */
+int chai_decode_attention_shared_v(const void *q, const void *k_compact, const void *v_compact,
+                                   const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H,
+                                   int k, int T, int Tc_cap, int Tv_cap, int d, int dtype, float scale,
+                                   float *out, void *workspace, size_t workspace_bytes, void *stream);
+int chai_append_kv_shared_v(const void *k_new, const void *v_new, const int32_t *rep_heads, void *k_compact,
+                            void *v_compact, int B, int H, int k, int pos, int Tc_cap, int Tv_cap, int d,
+                            int dtype, void *stream);
 
 /*
  * Dense multi-head decode attention, the definition of Section 2

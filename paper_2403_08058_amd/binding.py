@@ -22,7 +22,8 @@ STATUS_NAMES = {0: "CHAI_OK", 1: "CHAI_ERR_NULL", 2: "CHAI_ERR_SHAPE", 3: "CHAI_
                 5: "CHAI_ERR_UNSUPPORTED", 6: "CHAI_ERR_HIP", 7: "CHAI_ERR_ALIGN"}
 
 EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_assign_clusters",
-           "chai_cluster_error", "chai_pick_cluster_count",
+           "chai_cluster_error", "chai_pick_cluster_count", "chai_closest_representatives",
+           "chai_decode_attention_shared_v", "chai_append_kv_shared_v",
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention",
            "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
            "chai_dense_decode_attention", "chai_prefill_workspace_bytes", "chai_prefill_attention",
@@ -59,6 +60,9 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_decode_values.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, vp, sz, vp]
     L.chai_decode_scores_timed.argtypes = L.chai_decode_scores.argtypes + [vp, vp]
     L.chai_decode_values_timed.argtypes = L.chai_decode_values.argtypes + [vp, vp]
+    L.chai_closest_representatives.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
+    L.chai_decode_attention_shared_v.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
+    L.chai_append_kv_shared_v.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     L.chai_prefill_workspace_bytes.restype = sz
     L.chai_prefill_workspace_bytes.argtypes = [ci, ci, ci, ci]
     L.chai_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
@@ -153,6 +157,17 @@ def chai_cluster_error(feat, head_to_cluster, k: int, sse=None, stream=None):
     return sse
 
 
+def chai_closest_representatives(feat, head_to_cluster, k: int, rep_heads=None, stream=None):
+    """feat [B,H,F] fp32, head_to_cluster [B,H] int32 -> rep_heads [B,k] int32: nearest-to-mean member per cluster."""
+    B, H, F = feat.shape
+    if rep_heads is None:
+        rep_heads = torch.empty((B, k), dtype=torch.int32, device=feat.device)
+    _check("chai_closest_representatives",
+           _lib.chai_closest_representatives(_ptr(feat), _ptr(head_to_cluster), B, H, F, k, _ptr(rep_heads),
+                                             _stream(stream)))
+    return rep_heads
+
+
 def chai_pick_cluster_count(mean_error, ks, tol: float) -> int:
     """Host-side plateau rule on an error curve (sequences of floats / ints)."""
     n = len(ks)
@@ -180,6 +195,29 @@ def chai_append_kv(k_new, v_new, rep_heads, k_compact, v_cache, pos: int, stream
     _check("chai_append_kv",
            _lib.chai_append_kv(_ptr(k_new), _ptr(v_new), _ptr(rep_heads), _ptr(k_compact), _ptr(v_cache), B, H, k, pos,
                                Tc_cap, T_cap, d, dtype_code(k_new), _stream(stream)))
+
+
+def chai_append_kv_shared_v(k_new, v_new, rep_heads, k_compact, v_compact, pos: int, stream=None):
+    B, H, d = k_new.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    Tv_cap = v_compact.shape[2]
+    _check("chai_append_kv_shared_v",
+           _lib.chai_append_kv_shared_v(_ptr(k_new), _ptr(v_new), _ptr(rep_heads), _ptr(k_compact), _ptr(v_compact), B,
+                                        H, k, pos, Tc_cap, Tv_cap, d, dtype_code(k_new), _stream(stream)))
+
+
+def chai_decode_attention_shared_v(q, k_compact, v_compact, head_to_cluster, rep_heads, T: int, scale: float, out,
+                                   workspace, stream=None):
+    """The variant that prunes values too: q [B,H,d], k_compact / v_compact [B,k,cap,d] -> out [B,H,d] fp32."""
+    B, H, d = q.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    Tv_cap = v_compact.shape[2]
+    _check("chai_decode_attention_shared_v",
+           _lib.chai_decode_attention_shared_v(_ptr(q), _ptr(k_compact), _ptr(v_compact), _ptr(head_to_cluster),
+                                               _ptr(rep_heads), B, H, k, T, Tc_cap, Tv_cap, d, dtype_code(q), scale,
+                                               _ptr(out), _ptr(workspace),
+                                               workspace.numel() * workspace.element_size(), _stream(stream)))
+    return out
 
 
 def chai_decode_workspace_bytes(B: int, H: int, k: int, T: int, d: int, dtype: int) -> int:

@@ -103,7 +103,20 @@ int chai_cluster_error(const float *feat, const int32_t *head_to_cluster, int B,
     if (H > 256 || F > 64 || (long long)k * F > 7168) return CHAI_ERR_UNSUPPORTED;
     if (cluster_error_lds_bytes(H, F, k) > 64 * 1024 - 64) return CHAI_ERR_UNSUPPORTED;
     if (B == 0) return CHAI_OK;
-    return hip_status(launch_cluster_error(feat, head_to_cluster, B, H, F, k, sse, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_cluster_error(feat, head_to_cluster, B, H, F, k, sse, nullptr,
+                                           static_cast<hipStream_t>(stream)));
+}
+
+int chai_closest_representatives(const float *feat, const int32_t *head_to_cluster, int B, int H, int F, int k,
+                                 int32_t *rep_heads, void *stream)
+{
+    if (!feat || !head_to_cluster || !rep_heads) return CHAI_ERR_NULL;
+    if (B < 0 || H < 1 || F < 1 || k < 1 || k > H) return CHAI_ERR_SHAPE;
+    if (H > 256 || F > 64 || (long long)k * F > 7168) return CHAI_ERR_UNSUPPORTED;
+    if (cluster_error_lds_bytes(H, F, k) > 64 * 1024 - 64) return CHAI_ERR_UNSUPPORTED;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_cluster_error(feat, head_to_cluster, B, H, F, k, nullptr, rep_heads,
+                                           static_cast<hipStream_t>(stream)));
 }
 
 int chai_pick_cluster_count(const double *mean_error, const int32_t *ks, int n, double tol, int32_t *k_out)
@@ -221,6 +234,48 @@ int chai_decode_attention(const void *q, const void *k_compact, const void *v_ca
     if (st != CHAI_OK) return st;
     return hip_status(launch_values(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, dtype, out, probs_out,
                                     workspace, plan, false, KernelEvents(), s));
+}
+
+int chai_append_kv_shared_v(const void *k_new, const void *v_new, const int32_t *rep_heads, void *k_compact,
+                            void *v_compact, int B, int H, int k, int pos, int Tc_cap, int Tv_cap, int d, int dtype,
+                            void *stream)
+{
+    if (!k_new || !v_new || !rep_heads || !k_compact || !v_compact) return CHAI_ERR_NULL;
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || k < 1 || k > H || pos < 0 || pos >= Tv_cap || pos >= Tc_cap || d < 1) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || B > kMaxGridYZ) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k_compact) || !aligned16(v_compact)) return CHAI_ERR_ALIGN;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_append_kv_shared(k_new, v_new, rep_heads, k_compact, v_compact, B, H, k, pos, Tc_cap,
+                                              Tv_cap, dtype, static_cast<hipStream_t>(stream)));
+}
+
+int chai_decode_attention_shared_v(const void *q, const void *k_compact, const void *v_compact,
+                                   const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k,
+                                   int T, int Tc_cap, int Tv_cap, int d, int dtype, float scale, float *out,
+                                   void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!q || !k_compact || !v_compact || !head_to_cluster || !rep_heads || !out) return CHAI_ERR_NULL;
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || k < 1 || k > H || T < 1 || T > Tc_cap || T > Tv_cap || d < 1) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || B > kMaxGridYZ || H > kMaxGridYZ) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k_compact) || !aligned16(v_compact) || !aligned16(out)) return CHAI_ERR_ALIGN;
+    // both caches hold k streams per batch row: the launch plan of k heads in k clusters
+    const DecodePlan plan = make_decode_plan(B, k, k, T);
+    if (B > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < plan.bytes))
+        return CHAI_ERR_WORKSPACE;
+    if (B == 0) return CHAI_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int e = launch_scores(q, k_compact, rep_heads, B, H, k, T, Tc_cap, dtype, scale, workspace, plan, false,
+                          KernelEvents{}, s);
+    if (e != (int)hipSuccess) return CHAI_ERR_HIP;
+    float *rows = reinterpret_cast<float *>(static_cast<char *>(workspace) + plan.off_rows);
+    MemberRows members;
+    members.head_to_cluster = head_to_cluster;
+    members.n_heads = H;
+    members.out_members = out;
+    return hip_status(launch_values(v_compact, nullptr, nullptr, B, k, k, T, Tv_cap, dtype, rows, nullptr, workspace,
+                                    plan, true, KernelEvents{}, s, &members));
 }
 
 int chai_dense_decode_attention(const void *q, const void *k_cache, const void *v_cache, int B, int H, int T,

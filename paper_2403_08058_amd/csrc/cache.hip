@@ -56,7 +56,37 @@ __global__ __launch_bounds__(64) void append_kernel(const uint4 *__restrict__ k_
     }
 }
 
+// grid (2k, B), one wave: rows 0..k-1 key rows, rows k..2k-1 value rows, both of the representatives.
+__global__ __launch_bounds__(64) void append_shared_kernel(const uint4 *__restrict__ k_new,
+                                                           const uint4 *__restrict__ v_new,
+                                                           const int32_t *__restrict__ rep,
+                                                           uint4 *__restrict__ k_compact, uint4 *__restrict__ v_compact,
+                                                           int H, int k, int pos, long long kc_stride,
+                                                           long long vc_stride, int vec_per_row)
+{
+    const int row = blockIdx.x, b = blockIdx.y, lane = threadIdx.x;
+    if (lane >= vec_per_row) return;
+    const int j = row < k ? row : row - k;
+    int r = rep[(size_t)b * k + j];
+    if (r < 0) return;
+    r = min(r, H - 1);
+    const size_t src = ((size_t)b * H + r) * vec_per_row + lane;
+    if (row < k) k_compact[((size_t)b * k + j) * kc_stride + (size_t)pos * vec_per_row + lane] = k_new[src];
+    else v_compact[((size_t)b * k + j) * vc_stride + (size_t)pos * vec_per_row + lane] = v_new[src];
+}
+
 }  // namespace
+
+int launch_append_kv_shared(const void *k_new, const void *v_new, const int32_t *rep, void *k_compact, void *v_compact,
+                            int B, int H, int k, int pos, int Tc_cap, int Tv_cap, int dtype, hipStream_t stream)
+{
+    const int vec_per_row = kHeadDim * (dtype == CHAI_BF16 ? 2 : 4) / 16;
+    append_shared_kernel<<<dim3(2 * k, B), 64, 0, stream>>>(
+        static_cast<const uint4 *>(k_new), static_cast<const uint4 *>(v_new), rep, static_cast<uint4 *>(k_compact),
+        static_cast<uint4 *>(v_compact), H, k, pos, (long long)Tc_cap * vec_per_row, (long long)Tv_cap * vec_per_row,
+        vec_per_row);
+    return (int)hipGetLastError();
+}
 
 int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
                           int T_cap, int Tc_cap, int dtype, hipStream_t stream)

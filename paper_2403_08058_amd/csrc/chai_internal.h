@@ -19,7 +19,7 @@ struct DecodePlan {
     int n_cs;        // score chunks per (b, cluster) = ceil(T / cs)
     int cp;          // tokens per workgroup of the value kernel
     int n_cp;        // value chunks per (b, head) = ceil(T / cp)
-    size_t off_scores, off_stats, off_partial, bytes;
+    size_t off_scores, off_stats, off_partial, off_rows, bytes;   // off_rows: [B,H,128] fp32 staging rows
 };
 
 DecodePlan make_decode_plan(int B, int H, int k, int T);
@@ -35,9 +35,16 @@ struct KernelEvents {
 int launch_scores(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap,
                   int dtype, float scale, void *workspace, const DecodePlan &plan, bool identity,
                   const KernelEvents &ev, hipStream_t stream);
+// members: when set, the H streams of `v` are compact (one per cluster) and the finished row of stream j goes
+// to out_members[b][h] of every head h (of n_heads) with head_to_cluster[b][h] == j; `out` is then staging.
+struct MemberRows {
+    const int32_t *head_to_cluster = nullptr;
+    int n_heads = 0;
+    float *out_members = nullptr;
+};
 int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
-                  const KernelEvents &ev, hipStream_t stream);
+                  const KernelEvents &ev, hipStream_t stream, const MemberRows *members = nullptr);
 
 int launch_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int dtype, int64_t qs,
                           int64_t ks, float scale, float *feat, hipStream_t stream);
@@ -46,8 +53,9 @@ int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const 
                            int32_t *h2c, int32_t *rep, int32_t *ncl, int32_t *iters, hipStream_t stream);
 size_t assign_clusters_lds_bytes(int H, int F, int k);
 
+// sse and rep_out (nearest-to-mean member of every cluster) are optional outputs of the same kernel
 int launch_cluster_error(const float *feat, const int32_t *h2c, int B, int H, int F, int k, double *sse,
-                         hipStream_t stream);
+                         int32_t *rep_out, hipStream_t stream);
 size_t cluster_error_lds_bytes(int H, int F, int k);
 
 // Clustered attention over a block of prompt positions (bf16 only).  identity = dense attention.  The events
@@ -59,6 +67,10 @@ size_t prefill_workspace_bytes(int B, int H, int k, int n_keys);
 
 int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
                           int T_cap, int Tc_cap, int dtype, hipStream_t stream);
+
+// Both caches compact (the variant that prunes values too): rows of the representatives only.
+int launch_append_kv_shared(const void *k_new, const void *v_new, const int32_t *rep, void *k_compact, void *v_compact,
+                            int B, int H, int k, int pos, int Tc_cap, int Tv_cap, int dtype, hipStream_t stream);
 
 int launch_append_kv(const void *k_new, const void *v_new, const int32_t *rep, void *k_compact, void *v_cache, int B,
                      int H, int k, int pos, int Tc_cap, int T_cap, int dtype, hipStream_t stream);

@@ -347,6 +347,21 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(const float *__restri
     out[orow * kHeadDim + threadIdx.x] = sum;
 }
 
+// Shared-value variant: the streams are compact (one per cluster); head h of n_heads takes the sum of the
+// partial rows of its cluster's stream.  grid = (n_heads, B), 128 threads.
+__global__ __launch_bounds__(kHeadDim) void combine_members_kernel(const float *__restrict__ partial, int n_cp,
+                                                                   const int32_t *__restrict__ h2c, int n_heads, int k,
+                                                                   float *__restrict__ out)
+{
+    const int h = blockIdx.x, b = blockIdx.y;
+    const int c = h2c[(size_t)b * n_heads + h];
+    if (c < 0 || c >= k) return;
+    const size_t srow = (size_t)b * k + c;
+    float sum = 0.f;
+    for (int s = 0; s < n_cp; ++s) sum += partial[(srow * n_cp + s) * kHeadDim + threadIdx.x];
+    out[((size_t)b * n_heads + h) * kHeadDim + threadIdx.x] = sum;
+}
+
 struct Workspace {
     float *scores;
     float2 *stats;
@@ -379,7 +394,7 @@ int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H
 template <bool BF16, bool IDENT, int NW, int NB>
 int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
-                  hipStream_t stream)
+                  hipStream_t stream, const MemberRows *members)
 {
     // the copy of the probabilities (tests, inspection) lives in an instantiation of its own so that the
     // production kernel has no store inside its streaming loop
@@ -394,7 +409,15 @@ int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
                               pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
                               static_cast<const float2 *>(w.stats), w.partial, out, probs_out);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess || pl.n_cp == 1) return (int)e;
+    if (e != hipSuccess) return (int)e;
+    if (members != nullptr) {
+        // one launch both adds the partial rows (n_cp = 1: the staged row itself) and hands them to the members
+        combine_members_kernel<<<dim3(members->n_heads, B), kHeadDim, 0, stream>>>(
+            pl.n_cp == 1 ? out : w.partial, pl.n_cp, members->head_to_cluster, members->n_heads, H,
+            members->out_members);
+        return (int)hipGetLastError();
+    }
+    if (pl.n_cp == 1) return (int)e;
     combine_kernel<<<dim3(B * H), kHeadDim, 0, stream>>>(w.partial, pl.n_cp, out);
     return (int)hipGetLastError();
 }
@@ -402,7 +425,7 @@ int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
 template <bool BF16, bool IDENT>
 int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                  float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
-                 hipStream_t stream)
+                 hipStream_t stream, const MemberRows *members)
 {
     // Workgroup shape (measured on MI355X): eight waves with one batch in flight each are 1-6 % faster than
     // four waves with two batches up to a few thousand tokens per workgroup; on long chunks four waves with
@@ -413,13 +436,13 @@ int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, i
     if (getenv("CHAI_NW")) nw = atoi(getenv("CHAI_NW"));
     if (getenv("CHAI_NB")) nb = atoi(getenv("CHAI_NB"));
     if (nw == 4 && nb == 3)
-        return values_launch<BF16, IDENT, 4, 3>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
+        return values_launch<BF16, IDENT, 4, 3>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members);
     if (nw == 16 && nb == 1)
-        return values_launch<BF16, IDENT, 16, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
+        return values_launch<BF16, IDENT, 16, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members);
 #endif
     if (nw == 4 && nb == 2)
-        return values_launch<BF16, IDENT, 4, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
-    return values_launch<BF16, IDENT, 8, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream);
+        return values_launch<BF16, IDENT, 4, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members);
+    return values_launch<BF16, IDENT, 8, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members);
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -460,6 +483,7 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
     pl.off_scores = off;  off = align_up(off + (size_t)B * k * T * sizeof(float), 256);
     pl.off_stats = off;   off = align_up(off + (size_t)B * k * max_n_cs * sizeof(float2), 256);
     pl.off_partial = off; off = align_up(off + (size_t)B * H * max_n_cp * kHeadDim * sizeof(float), 256);
+    pl.off_rows = off;    off = align_up(off + (size_t)B * H * kHeadDim * sizeof(float), 256);
     pl.bytes = off;
     return pl;
 }
@@ -478,15 +502,18 @@ int launch_scores(const void *q, const void *kc, const int32_t *rep, int B, int 
 
 int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
-                  const KernelEvents &ev, hipStream_t stream)
+                  const KernelEvents &ev, hipStream_t stream, const MemberRows *members)
 {
     const Workspace w(workspace, plan);
     if (dtype == CHAI_BF16)
-        return identity
-                   ? values_typed<true, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream)
-                   : values_typed<true, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream);
-    return identity ? values_typed<false, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream)
-                    : values_typed<false, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream);
+        return identity ? values_typed<true, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
+                                                   members)
+                        : values_typed<true, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
+                                                    members);
+    return identity ? values_typed<false, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
+                                                members)
+                    : values_typed<false, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
+                                                 members);
 }
 
 }  // namespace chai

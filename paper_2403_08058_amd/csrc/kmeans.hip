@@ -195,11 +195,14 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
 // Clustering error of a given partition (Section 3.2): grid (B), 256 threads.  Means per (cluster, coordinate)
 // by one thread each (members in head order), distance of every head to its cluster's mean by one thread each,
 // then thread 0 adds the distances cluster by cluster, heads ascending: the order of the sequential statement.
+// With rep_out, thread j also picks the member of cluster j nearest its mean (first of equals = lowest head,
+// -1 for an empty slot).  Either output may be NULL.
 // Dynamic LDS: means [k][F] fp64, distances [H] fp64, counts [k].
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(kBlock) void cluster_error_kernel(const float *__restrict__ feat,
                                                                const int32_t *__restrict__ h2c, int H, int F, int k,
-                                                               double *__restrict__ sse)
+                                                               double *__restrict__ sse,
+                                                               int32_t *__restrict__ rep_out)
 {
     extern __shared__ double lds[];
     double *mean = lds;                          // [k][F]
@@ -229,7 +232,19 @@ __global__ __launch_bounds__(kBlock) void cluster_error_kernel(const float *__re
         dist[h] = (j >= 0 && j < k) ? sqdist(X + (size_t)h * F, mean + (size_t)j * F, F) : 0.0;
     }
     __syncthreads();
-    if (tid == 0) {
+    if (rep_out != nullptr) {
+        for (int j = tid; j < k; j += kBlock) {
+            int best = -1;
+            double best_d = 0.0;
+            for (int h = 0; h < H; ++h)
+                if (lab[h] == j && (best < 0 || dist[h] < best_d)) {
+                    best = h;
+                    best_d = dist[h];
+                }
+            rep_out[(size_t)b * k + j] = best;
+        }
+    }
+    if (sse != nullptr && tid == 0) {
         double total = 0.0;
         for (int j = 0; j < k; ++j)
             for (int h = 0; h < H; ++h)
@@ -276,9 +291,10 @@ size_t cluster_error_lds_bytes(int H, int F, int k)
 }
 
 int launch_cluster_error(const float *feat, const int32_t *h2c, int B, int H, int F, int k, double *sse,
-                         hipStream_t stream)
+                         int32_t *rep_out, hipStream_t stream)
 {
-    cluster_error_kernel<<<dim3(B), kBlock, cluster_error_lds_bytes(H, F, k), stream>>>(feat, h2c, H, F, k, sse);
+    cluster_error_kernel<<<dim3(B), kBlock, cluster_error_lds_bytes(H, F, k), stream>>>(feat, h2c, H, F, k, sse,
+                                                                                        rep_out);
     return (int)hipGetLastError();
 }
 
