@@ -20,6 +20,8 @@
 
 #include <hip/hip_ext.h>
 
+#include <type_traits>
+
 namespace chai {
 
 namespace {
@@ -136,38 +138,63 @@ __global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t *__rest
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// grid (query tiles [largest first], max_groups, B), 512 threads.  IDENT: every head is its own cluster
-// (dense attention); the work list is not read.
+// Main kernel.  1-D grid of n_qt * n_slots * B workgroups of 512 threads; IDENT: every head is its own cluster
+// (dense attention) and the work list is not read.
+//
+// Workgroup -> work item: the hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each with an L2
+// of its own.  The ids are therefore re-numbered so that every XCD owns a contiguous range of (batch row, group)
+// pairs with all their query tiles (largest first): the tiles of one group stream the same keys and values and
+// now find them in the same L2.
+//
+// LDS (dynamic): three K tiles and two V^T tiles per member.  K runs one tile ahead of V^T because the scores of
+// a 32-key block are issued one block before its softmax (the matrix pipe works on the next block's scores while
+// the vector ALUs exponentiate this one), and the extra buffer of each kind lets tile t+2 / t+1 be written while
+// tile t is read: ONE barrier per 64-key tile.
 // ---------------------------------------------------------------------------------------------------------
+constexpr int kKBufs = 3, kVBufs = 2;
+constexpr size_t kKBufBytes = (size_t)kKTile * kKStride * 2;
+constexpr size_t kVBufBytes = (size_t)kHeadDim * kVStride * 2;      // one member
+constexpr size_t prefill_lds_bytes(bool ident) { return kKBufs * kKBufBytes + kVBufs * (ident ? 1 : kGroup) * kVBufBytes; }
+
 template <bool IDENT>
 __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict__ q, const char *__restrict__ kc,
                                                           const _Float16 *__restrict__ vt,
                                                           const int32_t *__restrict__ rep,
                                                           const int32_t *__restrict__ groups,
                                                           const int32_t *__restrict__ n_groups, int H, int k, int Tq,
-                                                          int q_start, int Tc_cap, int Tp, int max_groups, float scale,
-                                                          float *__restrict__ out)
+                                                          int q_start, int Tc_cap, int Tp, int n_qt, int n_slots,
+                                                          float scale, float *__restrict__ out)
 {
-    __shared__ __attribute__((aligned(16))) __bf16 k_lds[kKTile][kKStride];
-    __shared__ __attribute__((aligned(16))) _Float16 v_lds[kGroup][kHeadDim][kVStride];
+    constexpr int G = IDENT ? 1 : kGroup;
+    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
+    char *const k_lds = lds_raw;                                   // [kKBufs][kKTile][kKStride] bf16
+    char *const v_lds = lds_raw + kKBufs * kKBufBytes;             // [kVBufs][G][kHeadDim][kVStride] fp16
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 31, hl = lane >> 5;
-    const int qt = gridDim.x - 1 - blockIdx.x, gi = blockIdx.y, b = blockIdx.z;
 
-    int cluster, n_mem, heads[kGroup];
+    int qt, gi, b;
+    {
+        const unsigned n = blockIdx.x, N = gridDim.x;
+        const unsigned x = n & 7u, per = N >> 3, rem = N & 7u;
+        const unsigned item = x * per + min(x, rem) + (n >> 3);
+        qt = n_qt - 1 - (int)(item % (unsigned)n_qt);
+        const unsigned rest = item / (unsigned)n_qt;
+        gi = (int)(rest % (unsigned)n_slots);
+        b = (int)(rest / (unsigned)n_slots);
+    }
+
+    int cluster, n_mem, heads[G];
     if (IDENT) {
-        if (gi >= H) return;
         cluster = gi; n_mem = 1;
-#pragma unroll
-        for (int g = 0; g < kGroup; ++g) heads[g] = gi;
+        heads[0] = gi;
     } else {
         if (gi >= n_groups[b]) return;
-        const int32_t *gr = groups + ((size_t)b * max_groups + gi) * (2 + kGroup);
+        const int32_t *gr = groups + ((size_t)b * n_slots + gi) * (2 + kGroup);
         cluster = min(max(gr[0], 0), k - 1);
         n_mem = min(max(gr[1], 1), kGroup);
 #pragma unroll
-        for (int g = 0; g < kGroup; ++g) heads[g] = min(max(gr[2 + min(g, n_mem - 1)], 0), H - 1);
+        for (int g = 0; g < G; ++g) heads[g] = min(max(gr[2 + min(g, n_mem - 1)], 0), H - 1);
     }
     const int rhead = IDENT ? cluster : min(max(rep[(size_t)b * k + cluster], 0), H - 1);
 
@@ -178,7 +205,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     const int wave_last = q_start + min(i0 + kQWave - 1, Tq - 1);     // last position any lane of the wave sees
     const int wg_last = q_start + min(qt * kQTile + kQTile - 1, Tq - 1);
     const int n_tiles = wg_last / kKTile + 1;                // key tiles 0 .. n_tiles-1 cover positions <= wg_last
-    const bool wave_active = i0 < Tq;
+    const int n_hb = i0 < Tq ? wave_last / 32 + 1 : 0;       // 32-key blocks this wave works on (0: padding wave)
     const int n_keys = q_start + Tq;                         // keys that exist (rows past them are never read)
 
     // query fragments (B operand of S^T = K Q^T): Q[my_i][16*ks + 8*hl .. +7]
@@ -189,52 +216,47 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         for (int ks = 0; ks < kHeadDim / 16; ++ks) qf[ks].raw = *reinterpret_cast<const u32x4 *>(qrow + ks * 32);
     }
 
-    // global -> LDS staging: K tile = 1024 pieces of 16 bytes, V^T tile of a head = 128 rows x 8
-    // pieces (kStagePieces per thread each).  A tile is fetched into registers one iteration ahead of its use.
+    // global -> registers -> LDS staging: a K tile is 1024 pieces of 16 bytes, a V^T tile of one head 128 rows x 8
+    // pieces (kStagePieces per thread each).  A tile sits in registers for one iteration before it is written.
     const char *ksrc = kc + ((size_t)b * k + cluster) * (size_t)Tc_cap * (kHeadDim * 2);
-    const _Float16 *vsrc[kGroup];
+    const _Float16 *vsrc[G];
 #pragma unroll
-    for (int g = 0; g < kGroup; ++g) vsrc[g] = vt + ((size_t)b * H + heads[g]) * (size_t)kHeadDim * Tp;
-    u32x4 kreg[kStagePieces], vreg[kGroup][kStagePieces];
-    auto fetch = [&](int kt) {
+    for (int g = 0; g < G; ++g) vsrc[g] = vt + ((size_t)b * H + heads[g]) * (size_t)kHeadDim * Tp;
+    u32x4 kreg[kStagePieces], vreg[kStagePieces];      // vreg: one member's V^T tile at a time
+    auto fetch_k = [&](int kt) {
         const int key0 = kt * kKTile;
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
             kreg[i] = *reinterpret_cast<const u32x4 *>(ksrc + (size_t)min(key0 + row, n_keys - 1) * (kHeadDim * 2) + c * 16);
         }
+    };
+    auto fetch_v = [&](int kt, int g) {
+        const int key0 = kt * kKTile;
 #pragma unroll
-        for (int g = 0; g < kGroup; ++g) {
-            if (g < n_mem) {
-#pragma unroll
-                for (int i = 0; i < kStagePieces; ++i) {
-                    const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
-                    vreg[g][i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + (size_t)dd * Tp + key0 + c * 8);
-                }
-            }
+        for (int i = 0; i < kStagePieces; ++i) {
+            const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
+            vreg[i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + (size_t)dd * Tp + key0 + c * 8);
         }
     };
-    auto stage = [&]() {
+    auto stage_k = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
-            *reinterpret_cast<u32x4 *>(&k_lds[row][c * 8]) = kreg[i];
+            *reinterpret_cast<u32x4 *>(k_lds + buf * kKBufBytes + (row * kKStride + c * 8) * 2) = kreg[i];
         }
+    };
+    auto stage_v = [&](int buf, int g) {
 #pragma unroll
-        for (int g = 0; g < kGroup; ++g) {
-            if (g < n_mem) {
-#pragma unroll
-                for (int i = 0; i < kStagePieces; ++i) {
-                    const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
-                    *reinterpret_cast<u32x4 *>(&v_lds[g][dd][c * 8]) = vreg[g][i];
-                }
-            }
+        for (int i = 0; i < kStagePieces; ++i) {
+            const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
+            *reinterpret_cast<u32x4 *>(v_lds + (buf * G + g) * kVBufBytes + (dd * kVStride + c * 8) * 2) = vreg[i];
         }
     };
 
-    f32x16 acc[kGroup][kHeadDim / 32];
+    f32x16 acc[G][kHeadDim / 32];
 #pragma unroll
-    for (int g = 0; g < kGroup; ++g)
+    for (int g = 0; g < G; ++g)
 #pragma unroll
         for (int blk = 0; blk < kHeadDim / 32; ++blk)
 #pragma unroll
@@ -242,97 +264,174 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     float m_run = -INFINITY, l_run = 0.f;          // running maximum (log2 units) and denominator of this query
     const float scale2 = scale * kLog2e;
 
-    fetch(0);
-    for (int kt = 0; kt < n_tiles; ++kt) {
-        const int key0 = kt * kKTile;
-        __syncthreads();                        // everyone is done reading the previous tile
-        stage();
-        __syncthreads();
-        if (kt + 1 < n_tiles) fetch(kt + 1);    // in flight while this tile is computed
-        if (!wave_active || key0 > wave_last) continue;     // uniform per wave; the barriers are always reached
+    // S^T block: 32 keys (rows half*32 .. +31 of K buffer `buf`) x 32 queries
+    auto score_block = [&](int buf, int half) {
+        f32x16 st;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st[e] = 0.f;
+        const char *kb = k_lds + buf * kKBufBytes + ((half * 32 + r) * kKStride + hl * 8) * 2;
+#pragma unroll
+        for (int ks = 0; ks < kHeadDim / 16; ++ks) {
+            Frag16 kf;
+            kf.raw = *reinterpret_cast<const u32x4 *>(kb + ks * 32);
+            st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st, 0, 0, 0);
+        }
+        return st;
+    };
 
-        // The staged tile is consumed as two halves of 32 keys, each: scores -> softmax update -> values, so only
-        // one 32 x 32 score block and its probabilities are live at a time.
+    // One block (keys kbase .. kbase+31, scores st): online softmax and the product with the members' values from
+    // V^T buffer vbuf.  HAS_NEXT: the scores of the wave's next block (K buffer nbuf, half nhalf) are issued in the
+    // same stretch of code as the exponentials, one MFMA per handful of vector instructions, so that the matrix
+    // pipe is busy while this wave exponentiates; they are returned.
+    auto block = [&](f32x16 st, int kbase, int vbuf, int half, auto has_next, int nbuf, int nhalf) {
+        constexpr bool HAS_NEXT = decltype(has_next)::value;
+        // causal mask: only blocks that reach past the wave's first query need it (a real branch, uniform per
+        // wave -- the empty asm keeps the compiler from turning it into 32 selects on every block)
+        if (kbase + 31 > wave_first) {
+            asm volatile("" ::: "memory");
 #pragma unroll
-        for (int kb = 0; kb < kKTile / 32; ++kb) {
-            const int kbase = key0 + kb * 32;
-            if (kbase > wave_last) break;                            // uniform per wave
-            // S^T block: 32 keys x 32 queries
-            f32x16 st;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) st[e] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < kHeadDim / 16; ++ks) {
-                Frag16 kf;
-                kf.raw = *reinterpret_cast<const u32x4 *>(&k_lds[kb * 32 + r][ks * 16 + hl * 8]);
-                st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st, 0, 0, 0);
+            for (int e = 0; e < 16; ++e) {
+                const int key = kbase + (e >> 2) * 8 + hl * 4 + (e & 3);
+                st[e] = key <= q_abs ? st[e] : -INFINITY;
             }
-            // causal mask: only blocks that reach past the wave's first query need it (a real branch, uniform
-            // per wave -- the empty asm keeps the compiler from turning it into 32 selects on every block)
-            if (kbase + 31 > wave_first) {
-                asm volatile("" ::: "memory");
+        }
+        // maximum of the raw scores (scale > 0 is required); the scale, times log2 e, is folded into the
+        // exponent: p = exp2(s * scale2 - m)
+        float ext = st[0];
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int key = kbase + (e >> 2) * 8 + hl * 4 + (e & 3);
-                    st[e] = key <= q_abs ? st[e] : -INFINITY;
+        for (int e = 1; e < 16; ++e) ext = fmaxf(ext, st[e]);
+        float mx = ext * scale2;
+        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        // lazy reference: the running maximum only moves when a block exceeds it by more than kRescaleSlack, so
+        // most blocks skip the rescaling of the accumulators (p < 2^slack)
+        const bool need = mx > m_run + kRescaleSlack;
+        const float m_new = need ? mx : m_run;
+        const float alpha = need ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;   // exp2(-inf) = 0 at the start
+        if (__any(need)) {
+            l_run *= alpha;
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (g < n_mem)
+#pragma unroll
+                    for (int blk = 0; blk < kHeadDim / 32; ++blk)
+#pragma unroll
+                        for (int e = 0; e < 16; ++e) acc[g][blk][e] *= alpha;
+        }
+        m_run = m_new;
+
+        f32x16 s_next = st;
+        float rs = 0.f;
+        Frag16 pf[2];
+        if (HAS_NEXT) {
+            // Exponentials of this block and scores of the next one, written out in the issue order wanted: per
+            // step one MFMA of the next block's scores (its K fragment was requested two steps earlier) and the
+            // vector work of two probabilities.  The scheduling barriers keep the compiler from regrouping it
+            // into "all MFMAs, then all exponentials", which would leave the matrix pipe idle during the latter.
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s_next[e] = 0.f;
+            const char *kb = k_lds + nbuf * kKBufBytes + ((nhalf * 32 + r) * kKStride + hl * 8) * 2;
+            Frag16 kf[kHeadDim / 16];
+            kf[0].raw = *reinterpret_cast<const u32x4 *>(kb);
+            kf[1].raw = *reinterpret_cast<const u32x4 *>(kb + 32);
+#pragma unroll
+            for (int i = 0; i < kHeadDim / 16; ++i) {
+                if (i + 2 < kHeadDim / 16) kf[i + 2].raw = *reinterpret_cast<const u32x4 *>(kb + (i + 2) * 32);
+                s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i].bf, qf[i].bf, s_next, 0, 0, 0);
+#pragma unroll
+                for (int e = 2 * i; e < 2 * i + 2; ++e) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(st[e], scale2, -m_run));
+                    rs += p;
+                    pf[e >> 3].h[e & 7] = (_Float16)p;
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            // maximum of the raw scores (scale > 0 is required); the scale, times log2 e, is folded into the
-            // exponent: p = exp2(s * scale2 - m)
-            float ext = st[0];
-#pragma unroll
-            for (int e = 1; e < 16; ++e) ext = fmaxf(ext, st[e]);
-            float mx = ext * scale2;
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            // online softmax with a lazy reference: the running maximum only moves when a block exceeds it by
-            // more than kRescaleSlack, so most blocks skip the rescaling of the accumulators (p < 2^slack)
-            const bool need = mx > m_run + kRescaleSlack;
-            const float m_new = need ? mx : m_run;
-            const float alpha = need ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;   // exp2(-inf) = 0 at the start
-            if (__any(need)) {
-                l_run *= alpha;
-#pragma unroll
-                for (int g = 0; g < kGroup; ++g)
-                    if (g < n_mem)
-#pragma unroll
-                        for (int blk = 0; blk < kHeadDim / 32; ++blk)
-#pragma unroll
-                            for (int e = 0; e < 16; ++e) acc[g][blk][e] *= alpha;
-            }
-            m_run = m_new;
-            float rs = 0.f;
-            Frag16 pf[2];
+        } else {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const float p = __builtin_amdgcn_exp2f(fmaf(st[e], scale2, -m_run));
                 rs += p;
                 pf[e >> 3].h[e & 7] = (_Float16)p;
             }
-            rs += __shfl_xor(rs, 32);
-            l_run += rs;
-
-            // O^T[d][query] += V^T P^T for every member head
+        }
+        rs += __shfl_xor(rs, 32);
+        l_run += rs;
+        // O^T[d][query] += V^T P^T for every member head: fragment j = (blk, s) of a member, requested
+        // kVAhead MFMAs before its use so that the LDS latency hides behind the matrix pipe
 #pragma unroll
-            for (int g = 0; g < kGroup; ++g) {
-                if (g < n_mem) {
+        for (int g = 0; g < G; ++g) {
+            if (g < n_mem) {
+                const char *vb = v_lds + (vbuf * G + g) * kVBufBytes + (r * kVStride + half * 32 + 8 * hl) * 2;
+                constexpr int kFrags = 2 * (kHeadDim / 32), kVAhead = 3;
+                Frag16 vf[kFrags];
 #pragma unroll
-                    for (int blk = 0; blk < kHeadDim / 32; ++blk) {
+                for (int j = 0; j < kVAhead; ++j)
+                    vf[j].raw = *reinterpret_cast<const u32x4 *>(vb + ((j >> 1) * 32 * kVStride + 16 * (j & 1)) * 2);
 #pragma unroll
-                        for (int s = 0; s < 2; ++s) {
-                            Frag16 vf;
-                            vf.raw = *reinterpret_cast<const u32x4 *>(&v_lds[g][blk * 32 + r][kb * 32 + 16 * s + 8 * hl]);
-                            acc[g][blk] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf.h, pf[s].h, acc[g][blk], 0, 0, 0);
-                        }
-                    }
+                for (int j = 0; j < kFrags; ++j) {
+                    if (j + kVAhead < kFrags)
+                        vf[j + kVAhead].raw = *reinterpret_cast<const u32x4 *>(
+                            vb + (((j + kVAhead) >> 1) * 32 * kVStride + 16 * ((j + kVAhead) & 1)) * 2);
+                    acc[g][j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[j].h, pf[j & 1].h, acc[g][j >> 1], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
         }
+        return s_next;
+    };
+    const std::true_type with_next;
+    const std::false_type last_block;
+
+    // prologue: K(0), K(1), V(0) in LDS; K(2) and the first member's V(1) in registers
+    fetch_k(0);
+    fetch_v(0, 0);
+    stage_k(0);
+    stage_v(0, 0);
+    if (G > 1 && n_mem > 1) { fetch_v(0, 1); stage_v(0, 1); }
+    if (n_tiles > 1) { fetch_k(1); stage_k(1); }
+    if (n_tiles > 2) fetch_k(2);
+    if (n_tiles > 1) fetch_v(1, 0);
+    __syncthreads();
+    // every wave, padding waves included: the first use of the query fragments is then outside the loop, and the
+    // loop body never has to wait for the loads that filled them (nor, in their shadow, for the prefetches)
+    f32x16 s_cur = score_block(0, 0);
+
+    // Staging schedule of iteration kt (tile kt is computed): at the top K(kt+2) and the first member's V(kt+1) go
+    // from registers to LDS and K(kt+3) and the second member's V(kt+1) are requested; between the two blocks of
+    // the tile the second member's V(kt+1) is written and the first member's V(kt+2) requested.  One member's tile
+    // in registers at a time keeps the register count of two-member groups inside the budget.
+    int kb3 = 0, vb2 = 0;                      // kt % 3, kt % 2
+    for (int kt = 0; kt < n_tiles; ++kt) {
+        const int kb3_1 = kb3 == 2 ? 0 : kb3 + 1, kb3_2 = kb3_1 == 2 ? 0 : kb3_1 + 1;
+        const bool more = kt + 1 < n_tiles;
+        if (kt + 2 < n_tiles) stage_k(kb3_2);
+        if (more) stage_v(vb2 ^ 1, 0);
+        if (kt + 3 < n_tiles) fetch_k(kt + 3);
+        if (G > 1 && n_mem > 1) {
+            if (more) fetch_v(kt + 1, 1);
+        } else if (kt + 2 < n_tiles) {
+            fetch_v(kt + 2, 0);
+        }
+
+        const int hb = 2 * kt;                             // blocks hb (first half of the tile) and hb + 1
+        if (hb + 1 < n_hb) s_cur = block(s_cur, hb * 32, vb2, 0, with_next, kb3, 1);
+        else if (hb < n_hb) s_cur = block(s_cur, hb * 32, vb2, 0, last_block, 0, 0);
+
+        if (G > 1 && n_mem > 1) {
+            if (more) stage_v(vb2 ^ 1, 1);
+            if (kt + 2 < n_tiles) fetch_v(kt + 2, 0);
+        }
+
+        if (hb + 2 < n_hb) s_cur = block(s_cur, hb * 32 + 32, vb2, 1, with_next, kb3_1, 0);
+        else if (hb + 1 < n_hb) s_cur = block(s_cur, hb * 32 + 32, vb2, 1, last_block, 0, 0);
+        __syncthreads();                                   // tile kt is done with; tiles kt+1 / kt+2 are visible
+        kb3 = kb3_1;
+        vb2 ^= 1;
     }
 
-    if (!wave_active || my_i >= Tq) return;
+    if (n_hb == 0 || my_i >= Tq) return;
     const float inv = 1.0f / l_run;
 #pragma unroll
-    for (int g = 0; g < kGroup; ++g) {
+    for (int g = 0; g < G; ++g) {
         if (g < n_mem) {
             float *orow = out + (((size_t)b * H + heads[g]) * Tq + my_i) * kHeadDim;
 #pragma unroll
@@ -380,21 +479,34 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     vt_kernel<<<dim3(Tp / kKTile, H, B), 256, 0, stream>>>(static_cast<const char *>(v), H, T_cap, n_keys, Tp, vt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
+    // more than 64 KB of dynamic LDS has to be allowed once per kernel
+    static const hipError_t attr_ident = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<true>),
+                                                             hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                             (int)prefill_lds_bytes(true));
+    static const hipError_t attr_clustered = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<false>),
+                                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                                 (int)prefill_lds_bytes(false));
+    if (attr_ident != hipSuccess) return (int)attr_ident;
+    if (attr_clustered != hipSuccess) return (int)attr_clustered;
+    if ((long long)n_qt * max_groups * B > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    const unsigned int n_wg = (unsigned int)n_qt * (unsigned int)max_groups * (unsigned int)B;
     if (identity) {
-        hipExtLaunchKernelGGL(prefill_kernel<true>, dim3(n_qt, H, B), dim3(kPBlock), 0, stream, ev.start, ev.stop, 0,
-                              static_cast<const char *>(q), static_cast<const char *>(kc),
+        hipExtLaunchKernelGGL(prefill_kernel<true>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(true), stream, ev.start,
+                              ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc),
                               static_cast<const _Float16 *>(vt), static_cast<const int32_t *>(nullptr),
                               static_cast<const int32_t *>(nullptr), static_cast<const int32_t *>(nullptr), H, k, Tq,
-                              q_start, Tc_cap, Tp, max_groups, scale, out);
+                              q_start, Tc_cap, Tp, n_qt, max_groups, scale, out);
         return (int)hipGetLastError();
     }
-    prefill_plan_kernel<<<dim3(B), 256, (size_t)(H + 2 * k) * sizeof(int32_t), stream>>>(h2c, rep, H, k, max_groups, groups, n_groups);
+    prefill_plan_kernel<<<dim3(B), 256, (size_t)(H + 2 * k) * sizeof(int32_t), stream>>>(h2c, rep, H, k, max_groups,
+                                                                                        groups, n_groups);
     e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    hipExtLaunchKernelGGL(prefill_kernel<false>, dim3(n_qt, max_groups, B), dim3(kPBlock), 0, stream, ev.start, ev.stop,
-                          0, static_cast<const char *>(q), static_cast<const char *>(kc),
+    hipExtLaunchKernelGGL(prefill_kernel<false>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(false), stream, ev.start,
+                          ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc),
                           static_cast<const _Float16 *>(vt), rep, static_cast<const int32_t *>(groups),
-                          static_cast<const int32_t *>(n_groups), H, k, Tq, q_start, Tc_cap, Tp, max_groups, scale, out);
+                          static_cast<const int32_t *>(n_groups), H, k, Tq, q_start, Tc_cap, Tp, n_qt, max_groups, scale,
+                          out);
     return (int)hipGetLastError();
 }
 
