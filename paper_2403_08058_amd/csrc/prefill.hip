@@ -49,6 +49,16 @@ union Frag16 {            // 16 bytes seen as a raw load, bf16 x 8 or fp16 x 8
     f16x8 h;
 };
 
+// Both halves of a wave get x of lanes 0..31 and x of lanes 32..63 (lane l and lane l ^ 32 see the same pair, in
+// the same order): one v_permlane32_swap instead of a round trip through the LDS crossbar.
+__device__ __forceinline__ void both_halves(float x, float &lo, float &hi)
+{
+    const unsigned int bits = __float_as_uint(x);
+    const auto sw = __builtin_amdgcn_permlane32_swap(bits, bits, false, false);
+    lo = __uint_as_float(sw[0]);
+    hi = __uint_as_float(sw[1]);
+}
+
 // Position of key jj (0..15) inside its group of 16 in V^T: lane half hl of MFMA step s multiplies its
 // probability registers e = 0..7, which hold keys 16s + (e/4)*8 + hl*4 + e%4, with 8 consecutive halves.
 __device__ __forceinline__ int key_slot16(int r16) { return 8 * ((r16 & 7) >> 2) + 4 * (r16 >> 3) + (r16 & 3); }
@@ -300,8 +310,9 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         float ext = st[0];
 #pragma unroll
         for (int e = 1; e < 16; ++e) ext = fmaxf(ext, st[e]);
-        float mx = ext * scale2;
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        float mx_lo, mx_hi;
+        both_halves(ext * scale2, mx_lo, mx_hi);
+        const float mx = fmaxf(mx_lo, mx_hi);
         // lazy reference: the running maximum only moves when a block exceeds it by more than kRescaleSlack, so
         // most blocks skip the rescaling of the accumulators (p < 2^slack)
         const bool need = mx > m_run + kRescaleSlack;
@@ -353,25 +364,29 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
                 pf[e >> 3].h[e & 7] = (_Float16)p;
             }
         }
-        rs += __shfl_xor(rs, 32);
-        l_run += rs;
+        float rs_lo, rs_hi;
+        both_halves(rs, rs_lo, rs_hi);
+        l_run += rs_lo + rs_hi;
         // O^T[d][query] += V^T P^T for every member head: fragment j = (blk, s) of a member, requested
         // kVAhead MFMAs before its use so that the LDS latency hides behind the matrix pipe
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (g < n_mem) {
                 const char *vb = v_lds + (vbuf * G + g) * kVBufBytes + (r * kVStride + half * 32 + 8 * hl) * 2;
-                constexpr int kFrags = 2 * (kHeadDim / 32), kVAhead = 3;
+                constexpr int kBlks = kHeadDim / 32, kFrags = 2 * kBlks, kVAhead = 3;
+                // fragment j: value rows 32 * (j % kBlks) .., keys 16 * (j / kBlks) .. of the block; the two MFMAs
+                // that add into the same accumulator are kBlks apart
                 Frag16 vf[kFrags];
 #pragma unroll
                 for (int j = 0; j < kVAhead; ++j)
-                    vf[j].raw = *reinterpret_cast<const u32x4 *>(vb + ((j >> 1) * 32 * kVStride + 16 * (j & 1)) * 2);
+                    vf[j].raw = *reinterpret_cast<const u32x4 *>(vb + ((j % kBlks) * 32 * kVStride + 16 * (j / kBlks)) * 2);
 #pragma unroll
                 for (int j = 0; j < kFrags; ++j) {
                     if (j + kVAhead < kFrags)
                         vf[j + kVAhead].raw = *reinterpret_cast<const u32x4 *>(
-                            vb + (((j + kVAhead) >> 1) * 32 * kVStride + 16 * ((j + kVAhead) & 1)) * 2);
-                    acc[g][j >> 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[j].h, pf[j & 1].h, acc[g][j >> 1], 0, 0, 0);
+                            vb + (((j + kVAhead) % kBlks) * 32 * kVStride + 16 * ((j + kVAhead) / kBlks)) * 2);
+                    acc[g][j % kBlks] =
+                        __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[j].h, pf[j / kBlks].h, acc[g][j % kBlks], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
