@@ -26,7 +26,9 @@ namespace chai {
 
 namespace {
 
-constexpr int kGroup = 2;          // member heads that share one score tile inside a workgroup
+constexpr int kGroup = 2;          // member heads that share one score tile in the 8-wave kernel
+constexpr int kWide = 4;           // ... and in the 4-wave kernel for larger clusters
+constexpr int kRec = 2 + kWide;    // ints per work-list record: cluster, member count, members
 constexpr int kQWave = 32;         // query rows per wave
 constexpr int kPWaves = 8;         // waves per workgroup (two per SIMD: one's MFMAs overlap the other's VALU work)
 constexpr int kPBlock = kPWaves * 64;
@@ -64,8 +66,9 @@ __device__ __forceinline__ void both_halves(float x, float &lo, float &hi)
 __device__ __forceinline__ int key_slot16(int r16) { return 8 * ((r16 & 7) >> 2) + 4 * (r16 >> 3) + (r16 & 3); }
 
 // ---------------------------------------------------------------------------------------------------------
-// V^T: vt[b][h][dd][16*(t/16) + key_slot16(t%16)] = fp16(V[b][h][t][dd]) for t < n_keys, 0 up to Tp.
-// grid (Tp/64, H, B), 256 threads; a 64 x 128 tile goes through LDS.
+// V^T in blocks of 32 keys: vt[b][h][t/32][dd][16*((t%32)/16) + key_slot16(t%16)] = fp16(V[b][h][t][dd]) for
+// t < n_keys, 0 up to Tp (a multiple of 64).  A block is 8 KB of consecutive memory, so the main kernels stage it
+// with fully coalesced 16-byte loads.  grid (Tp/64, H, B), 256 threads; a 64 x 128 tile goes through LDS.
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void vt_kernel(const char *__restrict__ v, int H, int T_cap, int n_keys, int Tp,
                                                  _Float16 *__restrict__ vt)
@@ -84,25 +87,25 @@ __global__ __launch_bounds__(256) void vt_kernel(const char *__restrict__ v, int
         for (int e = 0; e < 8; ++e) tile[c8 * 8 + e][slot] = (_Float16)(float)x.bf[e];
     }
     __syncthreads();
-    _Float16 *dst = vt + ((size_t)b * H + h) * (size_t)kHeadDim * Tp + t0;
+    _Float16 *dst = vt + (((size_t)b * H + h) * (Tp / 32) + t0 / 32) * (size_t)(kHeadDim * 32);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const int idx = tid + i * 256, dd = idx >> 4, c4 = idx & 15;              // 4 keys = 8 bytes per item
-        const unsigned int lo = *reinterpret_cast<const unsigned int *>(&tile[dd][c4 * 4]);
-        const unsigned int hi = *reinterpret_cast<const unsigned int *>(&tile[dd][c4 * 4 + 2]);
-        *reinterpret_cast<uint2 *>(dst + (size_t)dd * Tp + c4 * 4) = make_uint2(lo, hi);
+        const int idx = tid + i * 256, c8 = idx & 7, dd = (idx >> 3) & (kHeadDim - 1), blk = idx >> 10;   // 4 keys each
+        const unsigned int lo = *reinterpret_cast<const unsigned int *>(&tile[dd][blk * 32 + c8 * 4]);
+        const unsigned int hi = *reinterpret_cast<const unsigned int *>(&tile[dd][blk * 32 + c8 * 4 + 2]);
+        *reinterpret_cast<uint2 *>(dst + ((size_t)blk * kHeadDim + dd) * 32 + c8 * 4) = make_uint2(lo, hi);
     }
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Work list: the heads of every cluster, in ascending order, cut into groups of at most kGroup.
-// groups[b][g] = {cluster, n, head_0 .. head_{kGroup-1}}; clusters in ascending order.  One workgroup per
+// Work list: the heads of every cluster, in ascending order, cut into groups of at most `gsize` (<= kWide).
+// groups[b][g] = {cluster, n, head_0 .. }, kRec ints per record; clusters in ascending order.  One workgroup per
 // batch row: the membership row is copied to LDS, thread j counts cluster j, thread h ranks head h among the
 // heads of its cluster, and every head writes its own slot.  Heads that name no live cluster are left out.
 // Dynamic LDS: (H + 2k) ints.
 // ---------------------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t *__restrict__ h2c,
-                                                           const int32_t *__restrict__ rep, int H, int k,
+                                                           const int32_t *__restrict__ rep, int H, int k, int gsize,
                                                            int max_groups, int32_t *__restrict__ groups,
                                                            int32_t *__restrict__ n_groups)
 {
@@ -122,27 +125,27 @@ __global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t *__rest
     __syncthreads();
     for (int j = tid; j < k; j += blockDim.x) {
         int first = 0;
-        for (int i = 0; i < j; ++i) first += (count[i] + kGroup - 1) / kGroup;
+        for (int i = 0; i < j; ++i) first += (count[i] + gsize - 1) / gsize;
         base[j] = first;
         if (j == k - 1) {
-            const int ng = first + (count[j] + kGroup - 1) / kGroup;
+            const int ng = first + (count[j] + gsize - 1) / gsize;
             n_groups[b] = ng < max_groups ? ng : max_groups;
         }
     }
     __syncthreads();
-    int32_t *g = groups + (size_t)b * max_groups * (2 + kGroup);
+    int32_t *g = groups + (size_t)b * max_groups * kRec;
     for (int h = tid; h < H; h += blockDim.x) {
         const int c = member[h];
         if (c < 0) continue;
         int rank = 0;
         for (int i = 0; i < h; ++i) rank += member[i] == c;
-        const int gi = base[c] + rank / kGroup, slot = rank % kGroup;
+        const int gi = base[c] + rank / gsize, slot = rank % gsize;
         if (gi >= max_groups) continue;
-        g[gi * (2 + kGroup) + 2 + slot] = h;
+        g[gi * kRec + 2 + slot] = h;
         if (slot == 0) {
             const int left = count[c] - rank;
-            g[gi * (2 + kGroup)] = c;
-            g[gi * (2 + kGroup) + 1] = left < kGroup ? left : kGroup;
+            g[gi * kRec] = c;
+            g[gi * kRec + 1] = left < gsize ? left : gsize;
         }
     }
 }
@@ -200,7 +203,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         heads[0] = gi;
     } else {
         if (gi >= n_groups[b]) return;
-        const int32_t *gr = groups + ((size_t)b * n_slots + gi) * (2 + kGroup);
+        const int32_t *gr = groups + ((size_t)b * n_slots + gi) * kRec;
         cluster = min(max(gr[0], 0), k - 1);
         n_mem = min(max(gr[1], 1), kGroup);
 #pragma unroll
@@ -242,11 +245,10 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         }
     };
     auto fetch_v = [&](int kt, int g) {
-        const int key0 = kt * kKTile;
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
-            vreg[i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + (size_t)dd * Tp + key0 + c * 8);
+            vreg[i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + ((size_t)(2 * kt + (c >> 2)) * kHeadDim + dd) * 32 + (c & 3) * 8);
         }
     };
     auto stage_k = [&](int buf) {
@@ -472,7 +474,7 @@ int prefill_max_groups(int H, int k) { return (H + kGroup - 1) / kGroup + k; }
 size_t prefill_workspace_bytes(int B, int H, int k, int n_keys)
 {
     const size_t Tp = ((size_t)n_keys + kKTile - 1) / kKTile * kKTile;
-    return round256((size_t)B * prefill_max_groups(H, k) * (2 + kGroup) * sizeof(int32_t)) +
+    return round256((size_t)B * prefill_max_groups(H, k) * kRec * sizeof(int32_t)) +
            round256((size_t)B * sizeof(int32_t)) + round256((size_t)B * H * kHeadDim * Tp * sizeof(_Float16));
 }
 
@@ -485,7 +487,7 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     const int max_groups = identity ? H : prefill_max_groups(H, k);
     char *ws = static_cast<char *>(workspace);
     int32_t *groups = reinterpret_cast<int32_t *>(ws);
-    ws += round256((size_t)B * prefill_max_groups(H, k) * (2 + kGroup) * sizeof(int32_t));
+    ws += round256((size_t)B * prefill_max_groups(H, k) * kRec * sizeof(int32_t));
     int32_t *n_groups = reinterpret_cast<int32_t *>(ws);
     ws += round256((size_t)B * sizeof(int32_t));
     _Float16 *vt = reinterpret_cast<_Float16 *>(ws);
@@ -513,7 +515,7 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
                               q_start, Tc_cap, Tp, n_qt, max_groups, scale, out);
         return (int)hipGetLastError();
     }
-    prefill_plan_kernel<<<dim3(B), 256, (size_t)(H + 2 * k) * sizeof(int32_t), stream>>>(h2c, rep, H, k, max_groups,
+    prefill_plan_kernel<<<dim3(B), 256, (size_t)(H + 2 * k) * sizeof(int32_t), stream>>>(h2c, rep, H, k, kGroup, max_groups,
                                                                                         groups, n_groups);
     e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
