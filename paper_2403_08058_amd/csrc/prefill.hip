@@ -13,9 +13,9 @@
 // probabilities is already in the B-operand layout of O^T += V^T P^T.  That second product runs in fp16 (P in
 // [0,256] keeps 11 bits instead of bf16's 8).  Its A operand needs 8 keys of one value column per lane, which a
 // row-major V cache cannot deliver, so a first kernel writes V^T once per call: fp16 (exact from bf16 inside
-// the fp16 range, |v| <= 65504), [d][T] per head, keys permuted inside every group of 16 into the order the
-// probability registers have, zero beyond the last key.  The main kernel then stages K and V^T tiles in LDS with
-// plain 16-byte copies and feeds every MFMA operand with one ds_read_b128.
+// the fp16 range, |v| <= 65504), in blocks of 32 keys x 128 columns, keys permuted inside every group of 16 into
+// the order the probability registers have, zero beyond the last key.  The main kernel then stages K and V^T
+// tiles in LDS with plain 16-byte copies and feeds every MFMA operand with one ds_read_b128.
 #include "chai_internal.h"
 
 #include <hip/hip_ext.h>

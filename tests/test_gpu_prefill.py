@@ -125,3 +125,61 @@ def test_prefill_argument_errors():
     kf = torch.zeros((B, kk, 32, 128), dtype=torch.float32, device="cuda")
     vf = torch.zeros((B, H, 32, 128), dtype=torch.float32, device="cuda")
     assert status(qf, kf, vf, h2c, rep, 0, 0.1, out, ws) == 5              # fp32 inputs not supported here
+
+
+@pytest.mark.parametrize("name,T", [("cfg2", 2048), ("cfg4", 512), ("cfg5", 32768)])
+def test_prefill_full_size_sampled(name, T):
+    """Prefill at the sizes bench.py --mode prefill times (same B, H, k, prompt length, positions 5..T-1, same
+    workspace sizing).  The oracle computes sampled (batch row, head, query rows) one by one from the bytes
+    downloaded from the device; properties that hold at any size: finite everywhere, members of a cluster with
+    identical values get identical rows."""
+    cfg = W.CONFIGS[name]
+    B, H, d = cfg.B, cfg.H, cfg.d
+    kk = cfg.ks[-1]
+    q_start, Tq = W.N_TOK, T - W.N_TOK
+    print(f"[full-size prefill] {name}: B={B} H={H} k={kk} T={T}", flush=True)
+    g = W.rng(cfg.seed, 0, "prefill-test")
+    if cfg.membership == "skewed":
+        h2c, rep = W.sized_membership(g, B, H, cfg.sizes)
+    else:
+        h2c, rep = W.random_membership(g, B, H, kk)
+    seed = cfg.seed * 4001
+    q = W.device_normal((B, H, Tq, d), cfg.dtype, seed + 1)
+    kfull = W.device_normal((B, H, T, d), cfg.dtype, seed + 2)
+    v = W.device_normal((B, H, T, d), cfg.dtype, seed + 3)
+    # two members of one cluster share their values: their output rows must then be equal bit for bit
+    b0 = 0
+    members = [np.nonzero(h2c[b0] == c)[0] for c in range(kk)]
+    pair = next(m for m in members if len(m) >= 2)
+    v[b0, pair[1]] = v[b0, pair[0]]
+    hd, rd = W.host_to_torch(h2c), W.host_to_torch(rep)
+    kc = torch.empty((B, kk, T, d), dtype=torch.bfloat16, device="cuda")
+    C.chai_compact_kcache(kfull, rd, kc, T)
+    out = torch.full((B, H, Tq, d), float("nan"), dtype=torch.float32, device="cuda")
+    ws = torch.full((C.chai_prefill_workspace_bytes(B, H, H, T),), 0xFF, dtype=torch.uint8, device="cuda")
+    C.chai_prefill_attention(q, kc, v, hd, rd, q_start, cfg.scale, out, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    assert torch.equal(out[b0, pair[0]], out[b0, pair[1]])
+    gs = np.random.default_rng(cfg.seed + T)
+    rows = 6
+    worst = 0.0
+    for s in range(10):
+        b, h = int(gs.integers(B)), int(gs.integers(H))
+        # blocks of rows at the start, around tile edges and at the end of the prompt
+        i0 = [0, 250, Tq - rows, int(gs.integers(Tq - rows)), int(gs.integers(Tq - rows))][s % 5]
+        i0 = max(min(i0, Tq - rows), 0)
+        c = int(h2c[b, h]); r = int(rep[b, c])
+        n = q_start + i0 + rows                                # keys the last sampled row sees
+        qh = W.torch_to_host_bits(q[b, r, i0:i0 + rows])       # [rows, d]
+        kh = W.torch_to_host_bits(kfull[b, r, :n])
+        vh = W.torch_to_host_bits(v[b, h, :n])
+        q2 = np.stack([qh, np.zeros_like(qh)])[None]           # head 0 = representative, head 1 = the sampled head
+        k2 = np.stack([kh, np.zeros_like(kh)])[None]
+        v2 = np.stack([np.zeros_like(vh), vh])[None]
+        ref = O.clustered_prefill(q2, k2, v2, np.zeros((1, 2), np.int32), np.zeros((1, 1), np.int32), q_start + i0,
+                                  cfg.scale)[0, 1]
+        ok, ratio = G.rows_close(out[b, h, i0:i0 + rows].cpu().numpy(), ref, RTOL_PREFILL)
+        assert ok, f"{name} (b={b}, h={h}, rows {i0}..): err/allowed {ratio:.3g}"
+        worst = max(worst, ratio)
+    print(f"worst err/allowed = {worst:.3f}")
