@@ -138,7 +138,7 @@ def test_prefill_full_size_sampled(name, T):
     kk = cfg.ks[-1]
     q_start, Tq = W.N_TOK, T - W.N_TOK
     print(f"[full-size prefill] {name}: B={B} H={H} k={kk} T={T}", flush=True)
-    g = W.rng(cfg.seed, 0, "prefill-test")
+    g = W.rng(cfg.seed, 0, "member", extra=7)
     if cfg.membership == "skewed":
         h2c, rep = W.sized_membership(g, B, H, cfg.sizes)
     else:
