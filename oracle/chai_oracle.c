@@ -17,7 +17,8 @@
  * reductions to dense attention, brute-force k-means over all partitions,
  * an independent Lloyd implementation with the same start, index gathers,
  * the shared-value ablation against dense attention of the representative,
- * the nearest-to-mean representative against hand-worked cases and numpy.
+ * the nearest-to-mean representative against hand-worked cases and numpy,
+ * the representatives' projections against a library contraction.
  * Unpinned: nothing in this file.  (How well clustered attention
  * approximates dense attention on trained models is not computed here at
  * all; it needs weights and datasets.)
@@ -612,6 +613,59 @@ int chai_oracle_kmeans(const float *feat, int B, int H, int F, int k, const int3
         if (sse) sse[b] = partition_error(X, head_to_cluster + (int64_t)b * H, H, F, k, centre);
     }
     free(centre); free(dmin); free(assign); free(prev); free(count); free(label);
+    return 0;
+}
+
+/*
+ * Query / key projections of the representatives only (Fig. 3 and Section
+ * 3.5: in clustered attention the query and key vectors of the other heads
+ * are not needed, so their share of the projection is not computed; the
+ * keys go straight into the pruned cache).  For every batch row b, cluster
+ * slot j with representative r = rep_heads[b][j] >= 0, token i < Tn and
+ * coordinate c < d:
+ *     q_rep[b][j][i][c] = sum_e x[b][i][e] * w_q[r*d + c][e]
+ *     k_rep[b][j][i][c] = sum_e x[b][i][e] * w_k[r*d + c][e]
+ * x [B,Tn,D]; w_q, w_k [H*d, D] (one row per output feature, the layout of
+ * a linear layer's weight); outputs [B,k,Tn,d] in double, unrounded (slots
+ * with rep_heads = -1 are filled with NaN).  No bias (LLaMa has none; a
+ * model with one adds it afterwards).
+ */
+int chai_oracle_project_qk(const void *x, const void *w_q, const void *w_k, const int32_t *rep_heads,
+                           int B, int H, int k, int Tn, int D, int d, int dtype,
+                           double *q_rep, double *k_rep)
+{
+    if (!x || !w_q || !w_k || !rep_heads || !q_rep || !k_rep) return 1;
+    if (B < 0 || H < 1 || k < 1 || k > H || Tn < 1 || D < 1 || d < 1) return 2;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return 3;
+    for (int64_t i = 0; i < (int64_t)B * k; ++i)
+        if (rep_heads[i] >= H) return 2;
+
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        for (int j = 0; j < k; ++j) {
+            int r = rep_heads[(int64_t)b * k + j];
+            for (int i = 0; i < Tn; ++i) {
+                int64_t xoff = ((int64_t)b * Tn + i) * D;
+                int64_t ooff = (((int64_t)b * k + j) * Tn + i) * d;
+                for (int c = 0; c < d; ++c) {
+                    if (r < 0) {
+                        q_rep[ooff + c] = NAN;
+                        k_rep[ooff + c] = NAN;
+                        continue;
+                    }
+                    int64_t woff = ((int64_t)r * d + c) * D;
+                    double aq = 0.0, ak = 0.0;
+                    for (int e = 0; e < D; ++e) {
+                        double xe = load_elem(x, xoff + e, dtype);
+                        aq += xe * load_elem(w_q, woff + e, dtype);
+                        ak += xe * load_elem(w_k, woff + e, dtype);
+                    }
+                    q_rep[ooff + c] = aq;
+                    k_rep[ooff + c] = ak;
+                }
+            }
+        }
+    }
     return 0;
 }
 

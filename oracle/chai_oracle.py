@@ -46,6 +46,7 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.chai_oracle_kmeans.argtypes = [vp, ci, ci, ci, ci, i32p, ci, i32p, i32p, i32p, i32p, vp]
     L.chai_oracle_cluster_error.argtypes = [vp, i32p, ci, ci, ci, ci, vp]
     L.chai_oracle_pick_cluster_count.argtypes = [vp, i32p, ci, cd, vp]
+    L.chai_oracle_project_qk.argtypes = [vp, vp, vp, i32p, ci, ci, ci, ci, ci, ci, ci, vp, vp]
     L.chai_oracle_compact_kcache.argtypes = [vp, i32p, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     L.chai_oracle_append_kv.argtypes = [vp, vp, i32p, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci]
     return L
@@ -234,6 +235,24 @@ def pick_cluster_count(err, ks, tol):
     out = np.zeros((1,), np.int32)
     _check(lib().chai_oracle_pick_cluster_count(_p(err), _p(ks), len(ks), float(tol), _p(out)), "pick_cluster_count")
     return int(out[0])
+
+
+def project_qk(x, w_q, w_k, rep_heads, d):
+    """x [B,Tn,D]; w_q, w_k [H*d, D]; rep_heads [B,k].  Returns (q_rep, k_rep), each [B,k,Tn,d] f64, unrounded."""
+    x, w_q, w_k = _c(x), _c(w_q), _c(w_k)
+    dt = _dtype_code(x)
+    assert _dtype_code(w_q) == dt and _dtype_code(w_k) == dt
+    B, Tn, D = x.shape
+    H = w_q.shape[0] // d
+    assert w_q.shape == (H * d, D) and w_k.shape == (H * d, D)
+    rep = _c(rep_heads, np.int32)
+    k = rep.shape[1]
+    assert rep.shape == (B, k)
+    q_rep = np.empty((B, k, Tn, d), np.float64)
+    k_rep = np.empty((B, k, Tn, d), np.float64)
+    _check(lib().chai_oracle_project_qk(_p(x), _p(w_q), _p(w_k), _p(rep), B, H, k, Tn, D, d, dt, _p(q_rep), _p(k_rep)),
+           "project_qk")
+    return q_rep, k_rep
 
 
 def compact_kcache(k_full, rep_heads, T, Tc_cap=None, k_compact=None, want_src_rows=False):

@@ -513,6 +513,44 @@ def pin_cluster_error_and_count():
 
 
 # ----------------------------------------------------------------------------------------------
+# projection pins
+# ----------------------------------------------------------------------------------------------
+def pin_projection_of_representatives():
+    # hand-worked: D = 2, d = 1, H = 3: w_q rows (1,0),(0,1),(1,1); w_k rows (2,0),(0,3),(1,-1); token x = (5,7)
+    x = np.array([[[5.0, 7.0], [1.0, -1.0]]], np.float32)
+    w_q = np.array([[1.0, 0.0], [0.0, 1.0], [1.0, 1.0]], np.float32)
+    w_k = np.array([[2.0, 0.0], [0.0, 3.0], [1.0, -1.0]], np.float32)
+    q, k = O.project_qk(x, w_q, w_k, np.array([[2, 0]], np.int32), 1)
+    assert q[0, :, :, 0].tolist() == [[12.0, 0.0], [5.0, 1.0]]          # slot 0 = head 2, slot 1 = head 0
+    assert k[0, :, :, 0].tolist() == [[-2.0, 2.0], [10.0, 2.0]]
+    # library contraction, fp32 and bf16 storage, an unused slot, heads that are nobody's representative poisoned
+    for seed, dt in [(71, W.F32), (72, W.BF16)]:
+        g = np.random.default_rng(seed)
+        B, H, kk, Tn, D, d = 2, 6, 3, 5, 24, 4
+        x = W.normal(g, (B, Tn, D), dt)
+        w_q, w_k = W.normal(g, (H * d, D), dt), W.normal(g, (H * d, D), dt)
+        _, rep = W.random_membership(g, B, H, kk)
+        rep[1, 2] = -1
+        q, k = O.project_qk(x, w_q, w_k, rep, d)
+        x64 = W.as_f64(x)
+        wq64, wk64 = W.as_f64(w_q).reshape(H, d, D), W.as_f64(w_k).reshape(H, d, D)
+        for b in range(B):
+            for j in range(kk):
+                if rep[b, j] < 0:
+                    assert np.all(np.isnan(q[b, j])) and np.all(np.isnan(k[b, j]))
+                    continue
+                assert np.allclose(q[b, j], np.einsum("te,ce->tc", x64[b], wq64[rep[b, j]]), rtol=1e-13, atol=1e-13)
+                assert np.allclose(k[b, j], np.einsum("te,ce->tc", x64[b], wk64[rep[b, j]]), rtol=1e-13, atol=1e-13)
+        used = {int(r) for r in rep.ravel() if r >= 0}
+        w_q2, w_k2 = w_q.copy().reshape(H, d, D), w_k.copy().reshape(H, d, D)
+        for h in range(H):
+            if h not in used:
+                w_q2[h], w_k2[h] = (0x7FC0 if dt == W.BF16 else np.nan), (0x7FC0 if dt == W.BF16 else np.nan)
+        q2, k2 = O.project_qk(x, w_q2.reshape(H * d, D), w_k2.reshape(H * d, D), rep, d)
+        assert np.array_equal(q2, q, equal_nan=True) and np.array_equal(k2, k, equal_nan=True)
+
+
+# ----------------------------------------------------------------------------------------------
 # cache pins
 # ----------------------------------------------------------------------------------------------
 def pin_compaction_is_a_gather():

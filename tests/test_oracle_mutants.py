@@ -86,6 +86,14 @@ MUTANTS = [
      "const int n = q_start + Tq;", 0, ["pin_prefill_matches_library_and_decode"]),
     ("prefill_query_row_stride", "int64_t qoff = (((int64_t)b * H + r) * Tq + i) * d;",
      "int64_t qoff = (((int64_t)b * H + r) * Tq + (Tq - 1 - i)) * d;", 0, ["pin_prefill_matches_library_and_decode"]),
+    ("projection_uses_slot_index_as_head", "int64_t woff = ((int64_t)r * d + c) * D;", "int64_t woff = ((int64_t)j * d + c) * D;", 0,
+     ["pin_projection_of_representatives"]),
+    ("projection_keys_from_query_weights", "ak += xe * load_elem(w_k, woff + e, dtype);", "ak += xe * load_elem(w_q, woff + e, dtype);", 0,
+     ["pin_projection_of_representatives"]),
+    ("projection_weight_read_column_major", "int64_t woff = ((int64_t)r * d + c) * D;", "int64_t woff = ((int64_t)r * d + c);", 0,
+     ["pin_projection_of_representatives"]),
+    ("projection_token_stride", "int64_t xoff = ((int64_t)b * Tn + i) * D;", "int64_t xoff = ((int64_t)b * Tn) * D + i;", 0,
+     ["pin_projection_of_representatives"]),
     ("compaction_source_stride", "int64_t src = ((int64_t)b * H + r) * T_cap + t;", "int64_t src = ((int64_t)b * H + r) * Tc_cap + t;", 0,
      ["pin_compaction_is_a_gather"]),
     ("compaction_copies_cluster_id_head", "int64_t src = ((int64_t)b * H + r) * T_cap + t;", "int64_t src = ((int64_t)b * H + j) * T_cap + t;", 0,
