@@ -32,9 +32,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--context", type=int, default=0, help="override the number of cached tokens (cfg4: 640 or 2048)")
-    ap.add_argument("--mode", default="decode", choices=["decode", "prefill", "shared-v"],
-                    help="decode (default, the headline metric), the clustered prefill attention, or the decode "
-                         "ablation that prunes values as well")
+    ap.add_argument("--mode", default="decode", choices=["decode", "prefill", "shared-v", "project"],
+                    help="decode (default, the headline metric), the clustered prefill attention, the decode "
+                         "ablation that prunes values as well, or the query/key projections of the representatives")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--no-phase-timing", action="store_true")
@@ -429,6 +429,117 @@ def shared_v_main(args, cfg, torch, C, W):
     print(json.dumps(result))
 
 
+def project_main(args, cfg, torch, C, W):
+    """Query/key projections of the representatives for a block of prompt tokens (positions 5..T-1 of every batch
+    row), all layers: the share of W_Q and W_K that clustered attention needs.  Dense baseline: the same kernel
+    with every head its own representative (the full projections)."""
+    import numpy as np
+    B, H, d, T = cfg.B, cfg.H, cfg.d, cfg.T
+    D = H * d
+    pos0, Tn = W.N_TOK, T - W.N_TOK
+    n_res = min(cfg.L, 4)
+    layers = []
+    for l in range(n_res):
+        k = cfg.ks[(l * cfg.L) // n_res if cfg.L > n_res else l]
+        seed = cfg.seed * 6007 + l
+        L = Layer()
+        L.k = k
+        g = W.rng(cfg.seed, l, "member")
+        _, rep = (W.sized_membership(g, B, H, cfg.sizes) if cfg.membership == "skewed"
+                  else W.random_membership(g, B, H, k))
+        L.rep = W.host_to_torch(rep)
+        L.q = W.device_normal((B, Tn, D), cfg.dtype, seed + 1)                        # activations
+        L.kfull = (W.device_normal((H * d, D), cfg.dtype, seed + 2) * 0.05).to(torch.bfloat16)     # w_q
+        L.v = (W.device_normal((H * d, D), cfg.dtype, seed + 3) * 0.05).to(torch.bfloat16)         # w_k
+        L.kc = torch.empty((B, k, T, d), dtype=torch.bfloat16, device="cuda")
+        layers.append(L)
+    q_out = torch.empty((B, H, Tn, d), dtype=torch.bfloat16, device="cuda")
+    k_all = torch.empty((B, H, T, d), dtype=torch.bfloat16, device="cuda")
+    ident = torch.arange(H, dtype=torch.int32, device="cuda").repeat(B, 1).contiguous()
+    ks_all = [layers[(l * n_res) // cfg.L].k for l in range(cfg.L)]
+
+    def clustered_step():
+        for l in range(cfg.L):
+            L = layers[(l * n_res) // cfg.L]
+            C.chai_project_qk(L.q, L.kfull, L.v, L.rep, q_out, L.kc, pos0)
+
+    def dense_step():
+        for l in range(cfg.L):
+            L = layers[(l * n_res) // cfg.L]
+            C.chai_project_qk(L.q, L.kfull, L.v, ident, q_out, k_all, pos0)
+
+    steps, warmup = max(args.steps // 4, 2), max(args.warmup // 2, 1)
+    dense_ms = None
+    if not args.no_dense:
+        dense_ms, _ = timed_steps(dense_step, max(steps // 2, 1), warmup, torch)
+    ms, wall_ms = timed_steps(clustered_step, steps, warmup, torch)
+    layer_flops = {k: 2.0 * Tn * D * (2 * k * d) * B for k in set(ks_all)}
+    flops = sum(layer_flops[k] for k in ks_all)
+    dense_flops = 2.0 * Tn * D * (2 * H * d) * B * cfg.L
+    hev = HipEvents()
+    recs = {}
+    for _ in range(max(steps // 2, 1)):
+        for l in range(cfg.L):
+            L = layers[(l * n_res) // cfg.L]
+            e0, e1 = hev.create(), hev.create()
+            C.chai_project_qk_timed(L.q, L.kfull, L.v, L.rep, q_out, L.kc, pos0, start_event=e0, stop_event=e1)
+            recs.setdefault(L.k, []).append((e0, e1))
+    torch.cuda.synchronize()
+    kern = {k: sum(hev.elapsed_ms(a, b) for a, b in v) / len(v) for k, v in recs.items()}
+    hev.close()
+    k_dom = max(set(ks_all), key=ks_all.count)
+    ach = layer_flops[k_dom] / (kern[k_dom] * 1e-3) / 1e12
+    result = {
+        "metric": "prompt tokens/s through the query/key projections of the representatives (all layers)",
+        "value": B * Tn / (ms * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{cfg.name} projection: {cfg.L} layers, model width {D} ({H} heads x d{d}), batch {B}, "
+                               f"{Tn} prompt tokens per row (positions {pos0}..{T - 1}), clusters/layer "
+                               f"{sorted(set(ks_all))}, {n_res} layers resident and visited in turn",
+                   "layers": cfg.L, "heads": H, "head_dim": d, "batch": B, "prompt": T},
+        "roofline": {"bound": "mfma", "kernel": f"project_kernel, layers with {k_dom} clusters", "achieved": ach,
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0, "traffic": None,
+                     "avg_launch_ms": kern[k_dom], "flops_per_launch": layer_flops[k_dom],
+                     "kernel_ms_by_clusters": {str(k): v for k, v in sorted(kern.items())}},
+        "TFLOPs_whole_step": flops / (ms * 1e-3) / 1e12,
+        "host_wall_ms_per_step": wall_ms,
+    }
+    if dense_ms is not None:
+        result["dense_projection"] = {"ms_per_step": dense_ms, "TFLOPs": dense_flops / (dense_ms * 1e-3) / 1e12,
+                                      "speedup_pruned_over_dense": dense_ms / ms,
+                                      "ideal_speedup_by_flops": dense_flops / flops}
+    if not args.no_cpu_baseline:
+        from oracle import chai_oracle as O
+        L = layers[-1]
+        C.chai_project_qk(L.q, L.kfull, L.v, L.rep, q_out, L.kc, pos0)
+        torch.cuda.synchronize()
+        wq, wk = W.torch_to_host_bits(L.kfull), W.torch_to_host_bits(L.v)
+        rep = L.rep.cpu().numpy()
+
+        def run_oracle(rows):
+            xh = W.torch_to_host_bits(L.q[:, Tn - rows:])
+            t0 = time.perf_counter()
+            q_ref, k_ref = O.project_qk(xh, wq, wk, rep, d)
+            dt = time.perf_counter() - t0
+            got_k = W.bf16_bits_to_f32(W.torch_to_host_bits(L.kc[:, :, T - rows:T])).astype(np.float64)
+            used = rep >= 0
+            err = float(np.max(np.abs(got_k[used] - k_ref[used]) /
+                               np.maximum(np.abs(k_ref[used]).max(-1, keepdims=True), 1e-30)))
+            return dt, err
+
+        dt0, _ = run_oracle(min(8, Tn))                      # calibration, then about 10 s of oracle time
+        rows = max(min(Tn, int(10.0 / max(dt0 / min(8, Tn), 1e-6))), 1)
+        dt, err = run_oracle(rows)
+        step_s = dt * (Tn / rows) * sum(ks_all) / L.k
+        result["cpu_baseline"] = {"value": B * Tn / step_s, "unit": "tokens/s", "cores": O.num_threads(), "kind": "oracle",
+                                  "sample": f"last {rows} of {Tn} tokens of every batch row of one layer ({dt:.1f} s of "
+                                            f"oracle time), scaled by token and cluster count to all layers",
+                                  "parity_worst_normwise_err": err,
+                                  "parity_note": "outputs are bf16: one rounding, up to 2^-8 of an element"}
+    print(json.dumps(result))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -456,6 +567,9 @@ def main():
         return
     if args.mode == "shared-v":
         shared_v_main(args, cfg, torch, C, W)
+        return
+    if args.mode == "project":
+        project_main(args, cfg, torch, C, W)
         return
 
     layers, t_member = build_layers(cfg, W, C, torch, keep_full_k=not args.no_dense)

@@ -355,6 +355,42 @@ int chai_dense_prefill_attention(const void *q, const void *k_cache, const void 
                                  int q_start, int T_cap, int d, int dtype, float scale, float *out,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/*
+ * Query and key projections of the representative heads only (Fig. 3 and
+ * Section 3.5: clustered attention needs the query and key vectors of one
+ * head per cluster, so the share of W_Q and W_K that belongs to the other
+ * heads is never multiplied; the new keys go straight into the pruned K
+ * cache).  For batch row b, slot j with r = rep_heads[b][j] >= 0, token
+ * i < Tn:
+ *   q_out[b][r][i][:]            = x[b][i][:] . w_q[r*d .. r*d+d-1][:]^T
+ *   k_compact[b][j][pos0 + i][:] = x[b][i][:] . w_k[r*d .. r*d+d-1][:]^T
+ * fp32 accumulation of exact bf16 products, one rounding (to nearest even)
+ * to bf16.  No bias term.
+ *
+ *   x         [B,Tn,D] bf16      activations of Tn tokens per batch row (a
+ *                                prompt block, or Tn = 1 for a decode step)
+ *   w_q, w_k  [H*d, D] bf16      one row per output feature (the layout of a
+ *                                linear layer's weight)
+ *   q_out     [B,H,Tn,d] bf16    rows of representatives written, others
+ *                                untouched (the layout chai_prefill_attention
+ *                                and, with Tn = 1, chai_decode_attention read)
+ *   k_compact [B,k,Tc_cap,d]     rows pos0 .. pos0+Tn-1 of used slots written
+ * bf16 only, d = 128, D a multiple of 64, Tn*D < 2^31 (otherwise
+ * CHAI_ERR_UNSUPPORTED); pos0 + Tn <= Tc_cap.  The saving is in flops (a
+ * fraction k/H of the dense projections); at Tn = 1 the call is bound by
+ * reading the representatives' weights.
+ *
+ * chai_project_qk_timed: two more arguments, hipEvent_t handles as void*
+ * that the runtime stamps with the kernel's begin and end (either may be
+ * NULL).
+ */
+int chai_project_qk(const void *x, const void *w_q, const void *w_k, const int32_t *rep_heads, int B, int H, int k,
+                    int Tn, int D, int d, int dtype, void *q_out, void *k_compact, int pos0, int Tc_cap,
+                    void *stream);
+int chai_project_qk_timed(const void *x, const void *w_q, const void *w_k, const int32_t *rep_heads, int B, int H,
+                          int k, int Tn, int D, int d, int dtype, void *q_out, void *k_compact, int pos0,
+                          int Tc_cap, void *stream, void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_as
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention",
            "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
            "chai_dense_decode_attention", "chai_prefill_workspace_bytes", "chai_prefill_attention",
-           "chai_prefill_attention_timed", "chai_dense_prefill_attention"]
+           "chai_prefill_attention_timed", "chai_dense_prefill_attention", "chai_project_qk", "chai_project_qk_timed"]
 
 
 class ChaiError(RuntimeError):
@@ -63,6 +63,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_closest_representatives.argtypes = [vp, vp, ci, ci, ci, ci, vp, vp]
     L.chai_decode_attention_shared_v.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     L.chai_append_kv_shared_v.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
+    L.chai_project_qk.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, ci, ci, vp]
+    L.chai_project_qk_timed.argtypes = L.chai_project_qk.argtypes + [vp, vp]
     L.chai_prefill_workspace_bytes.restype = sz
     L.chai_prefill_workspace_bytes.argtypes = [ci, ci, ci, ci]
     L.chai_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
@@ -218,6 +220,28 @@ def chai_decode_attention_shared_v(q, k_compact, v_compact, head_to_cluster, rep
                                                _ptr(out), _ptr(workspace),
                                                workspace.numel() * workspace.element_size(), _stream(stream)))
     return out
+
+
+def chai_project_qk_timed(x, w_q, w_k, rep_heads, q_out, k_compact, pos0: int, stream=None, start_event=None,
+                          stop_event=None):
+    """x [B,Tn,D], w_q / w_k [H*d, D], rep_heads [B,k] -> rows of representatives of q_out [B,H,Tn,d] and rows
+    pos0.. of k_compact [B,k,Tc_cap,d] (all bf16).  Events: raw hipEvent_t handles or None."""
+    B, Tn, D = x.shape
+    H, d = q_out.shape[1], q_out.shape[3]
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    _check("chai_project_qk_timed",
+           _lib.chai_project_qk_timed(_ptr(x), _ptr(w_q), _ptr(w_k), _ptr(rep_heads), B, H, k, Tn, D, d, dtype_code(x),
+                                      _ptr(q_out), _ptr(k_compact), pos0, Tc_cap, _stream(stream), start_event,
+                                      stop_event))
+
+
+def chai_project_qk(x, w_q, w_k, rep_heads, q_out, k_compact, pos0: int, stream=None):
+    B, Tn, D = x.shape
+    H, d = q_out.shape[1], q_out.shape[3]
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    _check("chai_project_qk",
+           _lib.chai_project_qk(_ptr(x), _ptr(w_q), _ptr(w_k), _ptr(rep_heads), B, H, k, Tn, D, d, dtype_code(x),
+                                _ptr(q_out), _ptr(k_compact), pos0, Tc_cap, _stream(stream)))
 
 
 def chai_decode_workspace_bytes(B: int, H: int, k: int, T: int, d: int, dtype: int) -> int:

@@ -23,6 +23,7 @@ SOURCES = {
     "cache.hip": [],
     # the softmax bookkeeping never sees NaNs (masked scores are -inf): drop the NaN-quieting copies around max
     "prefill.hip": ["-fno-honor-nans"],
+    "project.hip": [],
     # bit-exact k-means: no fused multiply-add, no reassociation
     "kmeans.hip": ["-ffp-contract=off", "-fno-fast-math"],
 }

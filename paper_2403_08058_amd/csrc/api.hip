@@ -295,6 +295,34 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
                                     true, KernelEvents(), s));
 }
 
+int chai_project_qk_timed(const void *x, const void *w_q, const void *w_k, const int32_t *rep_heads, int B, int H, int k,
+                          int Tn, int D, int d, int dtype, void *q_out, void *k_compact, int pos0, int Tc_cap,
+                          void *stream, void *start_event, void *stop_event)
+{
+    if (!x || !w_q || !w_k || !rep_heads || !q_out || !k_compact) return CHAI_ERR_NULL;
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || k < 1 || k > H || Tn < 1 || D < 1 || d < 1 || pos0 < 0) return CHAI_ERR_SHAPE;
+    if ((long long)pos0 + Tn > Tc_cap) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || dtype != CHAI_BF16 || D % 64 != 0 || (long long)Tn * D * 2 >= (1LL << 32) ||
+        (long long)kHeadDim * D * 2 >= (1LL << 32))
+        return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(w_q) || !aligned16(w_k) || !aligned16(q_out) || !aligned16(k_compact))
+        return CHAI_ERR_ALIGN;
+    if (B == 0) return CHAI_OK;
+    KernelEvents ev;
+    ev.start = static_cast<hipEvent_t>(start_event);
+    ev.stop = static_cast<hipEvent_t>(stop_event);
+    return hip_status(launch_project_qk(x, w_q, w_k, rep_heads, B, H, k, Tn, D, q_out, k_compact, pos0, Tc_cap, ev,
+                                        static_cast<hipStream_t>(stream)));
+}
+
+int chai_project_qk(const void *x, const void *w_q, const void *w_k, const int32_t *rep_heads, int B, int H, int k,
+                    int Tn, int D, int d, int dtype, void *q_out, void *k_compact, int pos0, int Tc_cap, void *stream)
+{
+    return chai_project_qk_timed(x, w_q, w_k, rep_heads, B, H, k, Tn, D, d, dtype, q_out, k_compact, pos0, Tc_cap, stream,
+                                 nullptr, nullptr);
+}
+
 size_t chai_prefill_workspace_bytes(int B, int H, int k, int n_keys)
 {
     if (B < 0 || H < 1 || k < 1 || k > H || n_keys < 1) return 0;

@@ -65,6 +65,11 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
                    void *workspace, bool identity, const KernelEvents &ev, hipStream_t stream);
 size_t prefill_workspace_bytes(int B, int H, int k, int n_keys);
 
+// Query and key projections of the representatives (bf16, d = 128, D a multiple of 64); the events cover the kernel.
+int launch_project_qk(const void *x, const void *w_q, const void *w_k, const int32_t *rep, int B, int H, int k, int Tn,
+                      int D, void *q_out, void *k_compact, int pos0, int Tc_cap, const KernelEvents &ev,
+                      hipStream_t stream);
+
 int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
                           int T_cap, int Tc_cap, int dtype, hipStream_t stream);
 

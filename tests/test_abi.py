@@ -24,7 +24,7 @@ def declared_functions():
 
 def test_header_symbols_exported(chai):
     names = declared_functions()
-    assert len(names) == 22 and "chai_assign_clusters" in names and "chai_compact_kcache" in names \
+    assert len(names) == 24 and "chai_assign_clusters" in names and "chai_compact_kcache" in names \
         and "chai_decode_attention" in names
     L = ctypes.CDLL(chai.LIB_PATH)
     for n in names:
@@ -96,6 +96,16 @@ def test_argument_checks_run_before_any_launch(chai):
     assert pf(q=fake + 2) == 7
     assert pf(B=0) == 0                         # empty batch: no-op
     assert L.chai_dense_prefill_attention(fake, fake, fake, 1, 32, 64, 0, 64, 128, 1, -1.0, fake, 0x1000, big, None) == 5
+    # projections of the representatives: x [B,Tn,D], weights [H*d, D]
+    pj = lambda **kw: L.chai_project_qk(*[kw.get(n, dflt) for n, dflt in (
+        ("x", fake), ("w_q", fake), ("w_k", fake), ("rep", fake), ("B", 1), ("H", 32), ("k", 8), ("Tn", 16), ("D", 4096),
+        ("d", 128), ("dtype", 1), ("q_out", fake), ("kc", fake), ("pos0", 0), ("Tc_cap", 64), ("stream", None))])
+    assert pj(w_k=None) == 1
+    assert pj(pos0=60) == 2                     # block runs past the compact cache
+    assert pj(dtype=7) == 3
+    assert pj(dtype=0) == 5 and pj(D=4000) == 5 and pj(d=64) == 5
+    assert pj(x=fake + 8) == 7
+    assert pj(B=0) == 0
     assert chai.chai_prefill_workspace_bytes(4, 32, 8, 100) == chai.chai_prefill_workspace_bytes(4, 32, 8, 128)
     assert chai.chai_prefill_workspace_bytes(4, 32, 8, 129) > chai.chai_prefill_workspace_bytes(4, 32, 8, 128)
 
