@@ -247,6 +247,28 @@ int chai_decode_values(const void *v_cache, const int32_t *head_to_cluster, cons
                        void *workspace, size_t workspace_bytes, void *stream);
 
 /*
+ * One decode step with the cache growth folded in (Section 2: the keys and
+ * values of the token being decoded join the cache, then it attends over
+ * all T positions; Section 3.5: only the representatives' keys are kept).
+ * Same result as chai_append_kv at position T-1 followed by
+ * chai_decode_attention over T positions, without the extra launch: the
+ * kernels that stream the caches take row T-1 from k_new / v_new and write
+ * it to the caches themselves.
+ *
+ *   k_new, v_new [B,H,d]   the new token's key and value rows (keys of
+ *                          representatives are read, values of all heads)
+ *   k_compact, v_cache     read for positions 0 .. T-2, row T-1 written
+ *   T                      context length INCLUDING the new token, >= 1
+ * Other arguments, limits and errors as chai_decode_attention (no
+ * probs_out).  The accumulation order of the new row differs from the
+ * two-call sequence, so outputs agree to rounding, not bit for bit.
+ */
+int chai_decode_step(const void *q, const void *k_new, const void *v_new, void *k_compact, void *v_cache,
+                     const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k, int T,
+                     int Tc_cap, int T_cap, int d, int dtype, float scale, float *out, void *workspace,
+                     size_t workspace_bytes, void *stream);
+
+/*
  * For callers that profile the two kernels: the same calls with two more
  * arguments, hipEvent_t handles passed as void* that the caller created with
  * timing enabled (either may be NULL).  The runtime stamps start_event when

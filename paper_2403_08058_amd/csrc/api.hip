@@ -236,6 +236,26 @@ int chai_decode_attention(const void *q, const void *k_compact, const void *v_ca
                                     workspace, plan, false, KernelEvents(), s));
 }
 
+int chai_decode_step(const void *q, const void *k_new, const void *v_new, void *k_compact, void *v_cache,
+                     const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k, int T, int Tc_cap,
+                     int T_cap, int d, int dtype, float scale, float *out, void *workspace, size_t workspace_bytes,
+                     void *stream)
+{
+    if (!k_new || !v_new || !head_to_cluster || !rep_heads) return CHAI_ERR_NULL;
+    DecodePlan plan;
+    int st = check_scores(q, k_compact, B, H, k, T, Tc_cap, d, dtype, workspace, workspace_bytes, &plan);
+    if (st == CHAI_OK) st = check_values(v_cache, out, B, H, k, T, T_cap, d, dtype, workspace, workspace_bytes, &plan);
+    if (st != CHAI_OK) return st;
+    if (!aligned16(k_new) || !aligned16(v_new)) return CHAI_ERR_ALIGN;
+    if (B == 0) return CHAI_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = hip_status(launch_scores(q, k_compact, rep_heads, B, H, k, T, Tc_cap, dtype, scale, workspace, plan, false,
+                                  KernelEvents(), s, k_new));
+    if (st != CHAI_OK) return st;
+    return hip_status(launch_values(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, dtype, out, nullptr,
+                                    workspace, plan, false, KernelEvents(), s, nullptr, v_new));
+}
+
 int chai_append_kv_shared_v(const void *k_new, const void *v_new, const int32_t *rep_heads, void *k_compact,
                             void *v_compact, int B, int H, int k, int pos, int Tc_cap, int Tv_cap, int d, int dtype,
                             void *stream)

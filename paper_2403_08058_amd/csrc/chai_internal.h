@@ -31,10 +31,12 @@ struct KernelEvents {
 };
 
 // Enqueue the two kernels of one decode call.  identity = true: every head is its own cluster and the maps
-// are not read (dense attention).  Each returns a hipError_t as int.
+// are not read (dense attention).  k_new / v_new [B,H,d] (clustered calls only): position T-1 is the token being
+// decoded, its rows are taken from there and written to the caches by the same kernels.  Each returns a
+// hipError_t as int.
 int launch_scores(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap,
                   int dtype, float scale, void *workspace, const DecodePlan &plan, bool identity,
-                  const KernelEvents &ev, hipStream_t stream);
+                  const KernelEvents &ev, hipStream_t stream, const void *k_new = nullptr);
 // members: when set, the H streams of `v` are compact (one per cluster) and the finished row of stream j goes
 // to out_members[b][h] of every head h (of n_heads) with head_to_cluster[b][h] == j; `out` is then staging.
 struct MemberRows {
@@ -44,7 +46,8 @@ struct MemberRows {
 };
 int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
-                  const KernelEvents &ev, hipStream_t stream, const MemberRows *members = nullptr);
+                  const KernelEvents &ev, hipStream_t stream, const MemberRows *members = nullptr,
+                  const void *v_new = nullptr);
 
 int launch_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int dtype, int64_t qs,
                           int64_t ks, float scale, float *feat, hipStream_t stream);

@@ -121,13 +121,18 @@ __device__ __forceinline__ int batch_row(int it, int w, int u, int rg)
 // ---------------------------------------------------------------------------------------------------------
 // Score kernel: s[b][j][t] = scale * q[b][rep(b,j)] . Kc[b][j][t], plus (max, sum of exp) per chunk of cs
 // tokens.  grid = (n_cs, k, B).
+// APPEND: the last position, T-1, is the token being decoded: its key is not in the cache yet.  The workgroup of
+// the last chunk takes it from k_new [B,H,d] (row of the representative), scores it, and writes it to the cache,
+// so that growing the cache costs no launch of its own.
 // ---------------------------------------------------------------------------------------------------------
-template <bool BF16, bool IDENT>
-__global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ q, const char *__restrict__ kc,
+template <bool BF16, bool IDENT, bool APPEND>
+__global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ q, const char *__restrict__ kc_in,
                                                        const int32_t *__restrict__ rep, int H, int k, int T,
                                                        int Tc_cap, float scale, int cs, int n_cs,
-                                                       float *__restrict__ scores, float2 *__restrict__ stats)
+                                                       float *__restrict__ scores, float2 *__restrict__ stats,
+                                                       const char *__restrict__ k_new)
 {
+    const char *const kc = kc_in;
     using TL = Tile<BF16>;
     __shared__ float s_lds[kMaxCs];
     __shared__ float red[kWaves];
@@ -140,9 +145,11 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
     const int cg = lane % TL::LPR, rg = lane / TL::LPR;
     const int t0 = chunk * cs;
     const int n = min(T, t0 + cs) - t0;      // >= 1 by construction of n_cs
+    const bool has_new = APPEND && chunk == n_cs - 1;        // this chunk ends with the token being decoded
+    const int n_old = has_new ? n - 1 : n;                   // rows that are in the cache already
 
     const char *kbase = kc + (((size_t)b * k + j) * Tc_cap + t0) * TL::ROW_BYTES + cg * 16;
-    const int n_it = (n + TL::BATCH * kWaves - 1) / (TL::BATCH * kWaves);
+    const int n_it = (n_old + TL::BATCH * kWaves - 1) / (TL::BATCH * kWaves);
 
     // Every load of the chunk is issued before anything else (cs <= 256: at most 2 batches per wave in bf16, 4
     // in fp32), including the lookup of the representative: the key stream of a cluster slot does not depend
@@ -154,7 +161,7 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
         if (it < n_it) {
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u)
-                raw[it][u] = stream16(kbase + (size_t)min(batch_row<BF16>(it, w, u, rg), n - 1) * TL::ROW_BYTES);
+                raw[it][u] = stream16(kbase + (size_t)min(batch_row<BF16>(it, w, u, rg), n_old - 1) * TL::ROW_BYTES);
         }
     }
 
@@ -180,8 +187,21 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
 #pragma unroll
                 for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
                 dot = row_sum<BF16>(dot);
-                if (cg == 0 && tl < n) s_lds[tl] = scale * dot;
+                if (cg == 0 && tl < n_old) s_lds[tl] = scale * dot;
             }
+        }
+    }
+    if (APPEND) {
+        if (has_new && w == 0 && rg == 0) {      // one lane group: the new key row of the representative
+            const u32x4 nraw = *reinterpret_cast<const u32x4 *>(k_new + ((size_t)b * H + r) * TL::ROW_BYTES + cg * 16);
+            float f[TL::EPL];
+            unpack(nraw, f);
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
+            dot = row_sum<BF16>(dot);
+            if (cg == 0) s_lds[n - 1] = scale * dot;
+            *reinterpret_cast<u32x4 *>(const_cast<char *>(kbase) + (size_t)(n - 1) * TL::ROW_BYTES) = nraw;
         }
     }
     __syncthreads();
@@ -206,7 +226,9 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
 // only workgroup barrier is the one that adds up the waves at the end.  With one chunk per head the sum goes to `out`, otherwise to a partial row that
 // combine_kernel adds up in chunk order.
 // ---------------------------------------------------------------------------------------------------------
-template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P>
+// APPEND: position T-1 is the token being decoded; the workgroup whose chunk ends there takes its value row from
+// v_new [B,H,d], weighs it like any other row and writes it to the cache.
+template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND>
 __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__ v,
                                                         const int32_t *__restrict__ h2c,
                                                         const int32_t *__restrict__ rep, int H, int k, int T,
@@ -214,7 +236,8 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
                                                         const float *__restrict__ scores,
                                                         const float2 *__restrict__ stats,
                                                         float *__restrict__ partial, float *__restrict__ out,
-                                                        float *__restrict__ probs_out)
+                                                        float *__restrict__ probs_out,
+                                                        const char *__restrict__ v_new)
 {
     using TL = Tile<BF16>;
     __shared__ float p_lds[NW][TL::BATCH];
@@ -225,7 +248,9 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     const int cg = lane % TL::LPR, rg = lane / TL::LPR;
     const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const int t0 = split * cp;
-    const int n = min(T, t0 + cp) - t0;
+    const int n_all = min(T, t0 + cp) - t0;
+    const bool has_new = APPEND && split == n_cp - 1;        // this chunk ends with the token being decoded
+    const int n = has_new ? n_all - 1 : n_all;               // rows that are in the cache already (may be 0)
     const int n_batches = (n + TL::BATCH - 1) / TL::BATCH;
     const int n_it = n_batches > w ? (n_batches - w + NW - 1) / NW : 0;     // batches of this wave
 
@@ -244,11 +269,13 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     // same number of loads whatever `it` is -- rows past the end are clamped to the last row and later
     // multiplied by p = 0 -- so the compiler can wait for exactly the batch it consumes and leave the younger
     // ones in flight (loads under a condition would force it to drain the whole queue at every merge point).
+    // last cached row of the chunk for rows past it (with APPEND a chunk may hold no cached row at all: row 0 then)
+    auto clamp_row = [&](int row) { return APPEND ? max(min(row, n - 1), 0) : min(row, n - 1); };
     auto request_v = [&](Batch &bt, int it) {
         const int r0 = (it * NW + w) * TL::BATCH + rg;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
-            bt.v[u] = stream16(vbase + ((unsigned int)min(r0 + u * TL::RPW, n - 1) * TL::ROW_BYTES + lane_off));
+            bt.v[u] = stream16(vbase + ((unsigned int)clamp_row(r0 + u * TL::RPW) * TL::ROW_BYTES + lane_off));
     };
 #pragma unroll
     for (int j = 0; j < NB; ++j) request_v(buf[j], j);
@@ -263,7 +290,7 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     // they still issue the load, of the last score, to keep the count fixed)
     auto request_s = [&](Batch &bt, int it) {
         const int tl = (it * NW + w) * TL::BATCH + lane;
-        bt.s = srow[min(tl, n - 1)];          // masked when it is consumed
+        bt.s = srow[clamp_row(tl)];           // masked when it is consumed
     };
 #pragma unroll
     for (int j = 0; j < NB; ++j) request_s(buf[j], j);
@@ -313,6 +340,18 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
             consume(buf[j], it0 + j);
             request_v(buf[j], it0 + j + NB);
             request_s(buf[j], it0 + j + NB);
+        }
+    }
+
+    if (APPEND) {
+        if (has_new && w == 0 && rg == 0) {      // one lane group: the new value row of this head
+            const u32x4 nraw = *reinterpret_cast<const u32x4 *>(v_new + ((size_t)b * H + h) * TL::ROW_BYTES + lane_off);
+            const float p = expf(srow[n] - M) * inv;
+            float f[TL::EPL];
+            unpack(nraw, f);
+#pragma unroll
+            for (int e = 0; e < TL::EPL; ++e) acc[e] = fmaf(p, f[e], acc[e]);
+            *reinterpret_cast<u32x4 *>(const_cast<char *>(vbase) + ((unsigned int)n * TL::ROW_BYTES + lane_off)) = nraw;
         }
     }
 
@@ -379,11 +418,18 @@ struct Workspace {
 // and the end of the kernel itself into a pair of events (both NULL for an ordinary launch).
 template <bool BF16, bool IDENT>
 int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap,
-                 float scale, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev, hipStream_t stream)
+                 float scale, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev, hipStream_t stream,
+                 const void *k_new)
 {
-    hipExtLaunchKernelGGL((score_kernel<BF16, IDENT>), dim3(pl.n_cs, k, B), dim3(kBlock), 0, stream, ev.start, ev.stop,
-                          0, static_cast<const char *>(q), static_cast<const char *>(kc), rep, H, k, T, Tc_cap, scale,
-                          pl.cs, pl.n_cs, w.scores, w.stats);
+    if (!IDENT && k_new != nullptr)
+        hipExtLaunchKernelGGL((score_kernel<BF16, false, true>), dim3(pl.n_cs, k, B), dim3(kBlock), 0, stream, ev.start,
+                              ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc), rep, H, k, T,
+                              Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats, static_cast<const char *>(k_new));
+    else
+        hipExtLaunchKernelGGL((score_kernel<BF16, IDENT, false>), dim3(pl.n_cs, k, B), dim3(kBlock), 0, stream,
+                              ev.start, ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc), rep, H,
+                              k, T, Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats,
+                              static_cast<const char *>(nullptr));
     return (int)hipGetLastError();
 }
 
@@ -394,20 +440,27 @@ int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H
 template <bool BF16, bool IDENT, int NW, int NB>
 int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
-                  hipStream_t stream, const MemberRows *members)
+                  hipStream_t stream, const MemberRows *members, const void *v_new)
 {
     // the copy of the probabilities (tests, inspection) lives in an instantiation of its own so that the
-    // production kernel has no store inside its streaming loop
-    if (probs_out != nullptr)
-        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, true>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0, stream,
-                              ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs,
-                              pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
-                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out);
+    // production kernel has no store inside its streaming loop; so does the variant that appends the new token
+    const char *no_new = nullptr;
+    if (!IDENT && v_new != nullptr)
+        hipExtLaunchKernelGGL((value_kernel<BF16, false, NW, NB, false, true>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0,
+                              stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
+                              pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
+                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out,
+                              static_cast<const char *>(v_new));
+    else if (probs_out != nullptr)
+        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, true, false>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0,
+                              stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
+                              pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
+                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out, no_new);
     else
-        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, false>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0, stream,
-                              ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap, pl.n_cs,
-                              pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
-                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out);
+        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, false, false>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0,
+                              stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
+                              pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
+                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out, no_new);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
     if (members != nullptr) {
@@ -425,7 +478,7 @@ int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
 template <bool BF16, bool IDENT>
 int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                  float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
-                 hipStream_t stream, const MemberRows *members)
+                 hipStream_t stream, const MemberRows *members, const void *v_new)
 {
     // Workgroup shape (measured on MI355X): eight waves with one batch in flight each are 1-6 % faster than
     // four waves with two batches up to a few thousand tokens per workgroup; on long chunks four waves with
@@ -436,13 +489,13 @@ int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, i
     if (getenv("CHAI_NW")) nw = atoi(getenv("CHAI_NW"));
     if (getenv("CHAI_NB")) nb = atoi(getenv("CHAI_NB"));
     if (nw == 4 && nb == 3)
-        return values_launch<BF16, IDENT, 4, 3>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members);
+        return values_launch<BF16, IDENT, 4, 3>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
     if (nw == 16 && nb == 1)
-        return values_launch<BF16, IDENT, 16, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members);
+        return values_launch<BF16, IDENT, 16, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
 #endif
     if (nw == 4 && nb == 2)
-        return values_launch<BF16, IDENT, 4, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members);
-    return values_launch<BF16, IDENT, 8, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members);
+        return values_launch<BF16, IDENT, 4, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+    return values_launch<BF16, IDENT, 8, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -490,30 +543,30 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
 
 int launch_scores(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap, int dtype,
                   float scale, void *workspace, const DecodePlan &plan, bool identity, const KernelEvents &ev,
-                  hipStream_t stream)
+                  hipStream_t stream, const void *k_new)
 {
     const Workspace w(workspace, plan);
     if (dtype == CHAI_BF16)
-        return identity ? scores_typed<true, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream)
-                        : scores_typed<true, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream);
-    return identity ? scores_typed<false, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream)
-                    : scores_typed<false, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream);
+        return identity ? scores_typed<true, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new)
+                        : scores_typed<true, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new);
+    return identity ? scores_typed<false, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new)
+                    : scores_typed<false, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new);
 }
 
 int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
-                  const KernelEvents &ev, hipStream_t stream, const MemberRows *members)
+                  const KernelEvents &ev, hipStream_t stream, const MemberRows *members, const void *v_new)
 {
     const Workspace w(workspace, plan);
     if (dtype == CHAI_BF16)
         return identity ? values_typed<true, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
-                                                   members)
+                                                   members, v_new)
                         : values_typed<true, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
-                                                    members);
+                                                    members, v_new);
     return identity ? values_typed<false, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
-                                                members)
+                                                members, v_new)
                     : values_typed<false, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
-                                                 members);
+                                                 members, v_new);
 }
 
 }  // namespace chai

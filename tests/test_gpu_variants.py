@@ -154,3 +154,46 @@ def test_shared_v_argument_errors():
     assert e.value.status == 2
     torch.cuda.synchronize()
     assert bool((out == 7.0).all())
+
+
+@pytest.mark.parametrize("dtype", [W.F32, W.BF16])
+@pytest.mark.parametrize("B,H,kk,T0,cap", [
+    (2, 32, 8, 255, 300),        # the new token is the last of a score chunk, then the first of the next
+    (3, 72, 16, 0, 16),          # the very first token: no cached row at all
+    (48, 32, 8, 127, 140),       # one value workgroup per head; new token starts a 128-row value chunk
+    (1, 32, 4, 1023, 1100),      # split value chunks + combine
+])
+def test_decode_step_folds_the_append(dtype, B, H, kk, T0, cap):
+    """chai_decode_step at contexts T0+1, T0+2, ..: outputs against the oracle on full caches that grew the same
+    way, and the caches themselves byte for byte against chai_append_kv's."""
+    g = np.random.default_rng(B * 11 + H + T0 + dtype)
+    h2c, rep = W.random_membership(g, B, H, kk)
+    if kk >= 8:
+        for b in range(B):
+            h2c[b][h2c[b] == 3] = 0                      # an unused slot
+        rep = W.representatives(h2c, kk)
+    kf, vf = W.normal(g, (B, H, cap, 128), dtype), W.normal(g, (B, H, cap, 128), dtype)
+    hd, rd = dev(h2c), dev(rep)
+    tdt = torch.float32 if dtype == W.F32 else torch.bfloat16
+    kc = torch.zeros((B, kk, cap, 128), dtype=tdt, device="cuda")
+    kc_ref = torch.zeros_like(kc)
+    vd, vd_ref = dev(vf), dev(vf)
+    if T0 > 0:
+        C.chai_compact_kcache(dev(kf), rd, kc, T0)
+        C.chai_compact_kcache(dev(kf), rd, kc_ref, T0)
+    ws = G.poisoned_workspace(B, H, kk, cap, 128, dtype)
+    out_whole, out = G.guarded((B, H, 128), torch.float32, float("nan"))
+    scale = float(np.float32(128 ** -0.5))
+    for s in range(3):
+        T = T0 + s + 1
+        kn, vn, qn = W.normal(g, (B, H, 128), dtype), W.normal(g, (B, H, 128), dtype), W.normal(g, (B, H, 128), dtype)
+        kf[:, :, T - 1], vf[:, :, T - 1] = kn, vn
+        C.chai_decode_step(dev(qn), dev(kn), dev(vn), kc, vd, hd, rd, T, scale, out, ws)
+        C.chai_append_kv(dev(kn), dev(vn), rd, kc_ref, vd_ref, T - 1)
+        torch.cuda.synchronize()
+        ref = O.clustered_decode(qn, kf, vf, h2c, rep, T, scale)
+        ok, worst = G.rows_close(out.cpu().numpy(), ref, G.RTOL[dtype])
+        assert ok, f"context {T}: worst err/allowed {worst:.3g}"
+        assert torch.equal(kc.view(torch.uint8), kc_ref.view(torch.uint8)), f"compact K cache differs at context {T}"
+        assert torch.equal(vd.view(torch.uint8), vd_ref.view(torch.uint8)), f"V cache differs at context {T}"
+    assert G.guards_intact(out_whole, (B, H, 128), float("nan"))
