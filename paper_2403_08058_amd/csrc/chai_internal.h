@@ -24,6 +24,20 @@ struct DecodePlan {
 
 DecodePlan make_decode_plan(int B, int H, int k, int T);
 
+// Kernels that use more than 64 KB of dynamic LDS must be told so once on every device they run on.  `done` is the
+// caller's per-kernel table (zero-initialised, one flag per device ordinal); a repeated call costs one hipGetDevice.
+constexpr int kMaxDevices = 64;
+inline hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, bool (&done)[kMaxDevices])
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < kMaxDevices && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && dev >= 0 && dev < kMaxDevices) done[dev] = true;
+    return e;
+}
+
 // Optional events the runtime stamps with the begin and the end of a kernel (NULL = not wanted).
 struct KernelEvents {
     hipEvent_t start = nullptr;

@@ -496,15 +496,11 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     vt_kernel<<<dim3(Tp / kKTile, H, B), 256, 0, stream>>>(static_cast<const char *>(v), H, T_cap, n_keys, Tp, vt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    // more than 64 KB of dynamic LDS has to be allowed once per kernel
-    static const hipError_t attr_ident = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<true>),
-                                                             hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                             (int)prefill_lds_bytes(true));
-    static const hipError_t attr_clustered = hipFuncSetAttribute(reinterpret_cast<const void *>(&prefill_kernel<false>),
-                                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
-                                                                 (int)prefill_lds_bytes(false));
-    if (attr_ident != hipSuccess) return (int)attr_ident;
-    if (attr_clustered != hipSuccess) return (int)attr_clustered;
+    static bool lds_ident[kMaxDevices], lds_clustered[kMaxDevices];
+    e = allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<true>), prefill_lds_bytes(true), lds_ident);
+    if (e != hipSuccess) return (int)e;
+    e = allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<false>), prefill_lds_bytes(false), lds_clustered);
+    if (e != hipSuccess) return (int)e;
     if ((long long)n_qt * max_groups * B > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     const unsigned int n_wg = (unsigned int)n_qt * (unsigned int)max_groups * (unsigned int)B;
     if (identity) {
