@@ -151,7 +151,7 @@ __global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t *__rest
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Main kernel.  1-D grid of n_qt * n_slots * B workgroups of 512 threads; IDENT: every head is its own cluster
+// Main kernel.  1-D grid of ceil(n_qt / 2) * n_slots * B workgroups of 512 threads; IDENT: every head is its own cluster
 // (dense attention) and the work list is not read.
 //
 // Workgroup -> work item: the hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each with an L2
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
                                                           const int32_t *__restrict__ rep,
                                                           const int32_t *__restrict__ groups,
                                                           const int32_t *__restrict__ n_groups, int H, int k, int Tq,
-                                                          int q_start, int Tc_cap, int Tp, int n_qt, int n_slots,
+                                                          int q_start, int Tc_cap, int Tp, int n_qt_arg, int n_slots,
                                                           float scale, float *__restrict__ out)
 {
     constexpr int G = IDENT ? 1 : kGroup;
@@ -186,13 +186,20 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 31, hl = lane >> 5;
 
-    int qt, gi, b;
+    // A work item is a PAIR of query tiles, the p-th largest and the p-th smallest of a group: under the causal
+    // mask tile q walks q+1 key tiles' worth of work, so every pair costs the same and the workgroups of a launch
+    // finish together instead of leaving a tail of long ones.
+    // (n_qt < 0: the launch is too small to fill the chip with pairs; every tile is then an item of its own.)
+    const bool paired = n_qt_arg > 0;
+    const int n_qt = paired ? n_qt_arg : -n_qt_arg;
+    const int n_pairs = paired ? (n_qt + 1) / 2 : n_qt;
+    int pi, gi, b;
     {
         const unsigned n = blockIdx.x, N = gridDim.x;
         const unsigned x = n & 7u, per = N >> 3, rem = N & 7u;
         const unsigned item = x * per + min(x, rem) + (n >> 3);
-        qt = n_qt - 1 - (int)(item % (unsigned)n_qt);
-        const unsigned rest = item / (unsigned)n_qt;
+        pi = (int)(item % (unsigned)n_pairs);
+        const unsigned rest = item / (unsigned)n_pairs;
         gi = (int)(rest % (unsigned)n_slots);
         b = (int)(rest / (unsigned)n_slots);
     }
@@ -211,6 +218,10 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     }
     const int rhead = IDENT ? cluster : min(max(rep[(size_t)b * k + cluster], 0), H - 1);
 
+    const float scale2 = scale * kLog2e;
+    const int n_pass = (paired && (n_qt - 1 - pi) > pi) ? 2 : 1;     // the middle tile of an odd count is alone
+    for (int pass = 0; pass < n_pass; ++pass) {
+    const int qt = pass == 0 ? n_qt - 1 - pi : pi;
     const int i0 = qt * kQTile + w * kQWave;                 // first query row of this wave (relative)
     const int my_i = i0 + r;                                 // this lane's query row
     const int q_abs = q_start + min(my_i, Tq - 1);           // its sequence position (clamped for padding rows)
@@ -235,34 +246,35 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     const _Float16 *vsrc[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) vsrc[g] = vt + ((size_t)b * H + heads[g]) * (size_t)kHeadDim * Tp;
-    u32x4 kreg[kStagePieces], vreg[kStagePieces];      // vreg: one member's V^T tile at a time
-    auto fetch_k = [&](int kt) {
+    u32x4 kreg[kStagePieces], vreg[kStagePieces];      // the loop's staging registers; vreg: one member's V^T tile at a time
+    typedef u32x4 Pieces[kStagePieces];
+    auto fetch_k = [&](int kt, Pieces &regs) {
         const int key0 = kt * kKTile;
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
-            kreg[i] = *reinterpret_cast<const u32x4 *>(ksrc + (size_t)min(key0 + row, n_keys - 1) * (kHeadDim * 2) + c * 16);
+            regs[i] = *reinterpret_cast<const u32x4 *>(ksrc + (size_t)min(key0 + row, n_keys - 1) * (kHeadDim * 2) + c * 16);
         }
     };
-    auto fetch_v = [&](int kt, int g) {
+    auto fetch_v = [&](int kt, int g, Pieces &regs) {
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
-            vreg[i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + ((size_t)(2 * kt + (c >> 2)) * kHeadDim + dd) * 32 + (c & 3) * 8);
+            regs[i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + ((size_t)(2 * kt + (c >> 2)) * kHeadDim + dd) * 32 + (c & 3) * 8);
         }
     };
-    auto stage_k = [&](int buf) {
+    auto stage_k = [&](int buf, const Pieces &regs) {
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
-            *reinterpret_cast<u32x4 *>(k_lds + buf * kKBufBytes + (row * kKStride + c * 8) * 2) = kreg[i];
+            *reinterpret_cast<u32x4 *>(k_lds + buf * kKBufBytes + (row * kKStride + c * 8) * 2) = regs[i];
         }
     };
-    auto stage_v = [&](int buf, int g) {
+    auto stage_v = [&](int buf, int g, const Pieces &regs) {
 #pragma unroll
         for (int i = 0; i < kStagePieces; ++i) {
             const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
-            *reinterpret_cast<u32x4 *>(v_lds + (buf * G + g) * kVBufBytes + (dd * kVStride + c * 8) * 2) = vreg[i];
+            *reinterpret_cast<u32x4 *>(v_lds + (buf * G + g) * kVBufBytes + (dd * kVStride + c * 8) * 2) = regs[i];
         }
     };
 
@@ -274,7 +286,6 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[g][blk][e] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;          // running maximum (log2 units) and denominator of this query
-    const float scale2 = scale * kLog2e;
 
     // S^T block: 32 keys (rows half*32 .. +31 of K buffer `buf`) x 32 queries
     auto score_block = [&](int buf, int half) {
@@ -398,15 +409,22 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     const std::true_type with_next;
     const std::false_type last_block;
 
-    // prologue: K(0), K(1), V(0) in LDS; K(2) and the first member's V(1) in registers
-    fetch_k(0);
-    fetch_v(0, 0);
-    stage_k(0);
-    stage_v(0, 0);
-    if (G > 1 && n_mem > 1) { fetch_v(0, 1); stage_v(0, 1); }
-    if (n_tiles > 1) { fetch_k(1); stage_k(1); }
-    if (n_tiles > 2) fetch_k(2);
-    if (n_tiles > 1) fetch_v(1, 0);
+    // prologue: K(0), K(1), V(0) into LDS, K(2) and the first member's V(1) into the loop's registers.  All requests
+    // go out before the first is waited for: the workgroup is alone on its CU, nothing else hides this latency.
+    {
+        Pieces k0, k1, v00, v01;
+        const bool two = G > 1 && n_mem > 1;
+        fetch_k(0, k0);
+        fetch_v(0, 0, v00);
+        if (two) fetch_v(0, 1, v01);
+        if (n_tiles > 1) fetch_k(1, k1);
+        if (n_tiles > 2) fetch_k(2, kreg);
+        if (n_tiles > 1) fetch_v(1, 0, vreg);
+        stage_k(0, k0);
+        stage_v(0, 0, v00);
+        if (two) stage_v(0, 1, v01);
+        if (n_tiles > 1) stage_k(1, k1);
+    }
     __syncthreads();
     // every wave, padding waves included: the first use of the query fragments is then outside the loop, and the
     // loop body never has to wait for the loads that filled them (nor, in their shadow, for the prefetches)
@@ -420,13 +438,13 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int kb3_1 = kb3 == 2 ? 0 : kb3 + 1, kb3_2 = kb3_1 == 2 ? 0 : kb3_1 + 1;
         const bool more = kt + 1 < n_tiles;
-        if (kt + 2 < n_tiles) stage_k(kb3_2);
-        if (more) stage_v(vb2 ^ 1, 0);
-        if (kt + 3 < n_tiles) fetch_k(kt + 3);
+        if (kt + 2 < n_tiles) stage_k(kb3_2, kreg);
+        if (more) stage_v(vb2 ^ 1, 0, vreg);
+        if (kt + 3 < n_tiles) fetch_k(kt + 3, kreg);
         if (G > 1 && n_mem > 1) {
-            if (more) fetch_v(kt + 1, 1);
+            if (more) fetch_v(kt + 1, 1, vreg);
         } else if (kt + 2 < n_tiles) {
-            fetch_v(kt + 2, 0);
+            fetch_v(kt + 2, 0, vreg);
         }
 
         const int hb = 2 * kt;                             // blocks hb (first half of the tile) and hb + 1
@@ -434,8 +452,8 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         else if (hb < n_hb) s_cur = block(s_cur, hb * 32, vb2, 0, last_block, 0, 0);
 
         if (G > 1 && n_mem > 1) {
-            if (more) stage_v(vb2 ^ 1, 1);
-            if (kt + 2 < n_tiles) fetch_v(kt + 2, 0);
+            if (more) stage_v(vb2 ^ 1, 1, vreg);
+            if (kt + 2 < n_tiles) fetch_v(kt + 2, 0, vreg);
         }
 
         if (hb + 2 < n_hb) s_cur = block(s_cur, hb * 32 + 32, vb2, 1, with_next, kb3_1, 0);
@@ -445,23 +463,25 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         vb2 ^= 1;
     }
 
-    if (n_hb == 0 || my_i >= Tq) return;
-    const float inv = 1.0f / l_run;
+    if (n_hb != 0 && my_i < Tq) {
+        const float inv = 1.0f / l_run;
 #pragma unroll
-    for (int g = 0; g < G; ++g) {
-        if (g < n_mem) {
-            float *orow = out + (((size_t)b * H + heads[g]) * Tq + my_i) * kHeadDim;
+        for (int g = 0; g < G; ++g) {
+            if (g < n_mem) {
+                float *orow = out + (((size_t)b * H + heads[g]) * Tq + my_i) * kHeadDim;
 #pragma unroll
-            for (int blk = 0; blk < kHeadDim / 32; ++blk)
+                for (int blk = 0; blk < kHeadDim / 32; ++blk)
 #pragma unroll
-                for (int v4 = 0; v4 < 4; ++v4) {
-                    float4 o;
-                    o.x = acc[g][blk][v4 * 4 + 0] * inv; o.y = acc[g][blk][v4 * 4 + 1] * inv;
-                    o.z = acc[g][blk][v4 * 4 + 2] * inv; o.w = acc[g][blk][v4 * 4 + 3] * inv;
-                    *reinterpret_cast<float4 *>(orow + blk * 32 + v4 * 8 + hl * 4) = o;
-                }
+                    for (int v4 = 0; v4 < 4; ++v4) {
+                        float4 o;
+                        o.x = acc[g][blk][v4 * 4 + 0] * inv; o.y = acc[g][blk][v4 * 4 + 1] * inv;
+                        o.z = acc[g][blk][v4 * 4 + 2] * inv; o.w = acc[g][blk][v4 * 4 + 3] * inv;
+                        *reinterpret_cast<float4 *>(orow + blk * 32 + v4 * 8 + hl * 4) = o;
+                    }
+            }
         }
     }
+    }   // the two query tiles of the pair
 }
 
 size_t round256(size_t x) { return (x + 255) / 256 * 256; }
@@ -501,14 +521,18 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     if (e != hipSuccess) return (int)e;
     e = allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<false>), prefill_lds_bytes(false), lds_clustered);
     if (e != hipSuccess) return (int)e;
-    if ((long long)n_qt * max_groups * B > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
-    const unsigned int n_wg = (unsigned int)n_qt * (unsigned int)max_groups * (unsigned int)B;
+    // a workgroup takes a large and a small query tile, unless that leaves fewer than two workgroups per CU
+    const bool paired = (long long)((n_qt + 1) / 2) * max_groups * B >= 512;
+    const int n_pairs = paired ? (n_qt + 1) / 2 : n_qt;
+    const int n_qt_arg = paired ? n_qt : -n_qt;
+    if ((long long)n_pairs * max_groups * B > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    const unsigned int n_wg = (unsigned int)n_pairs * (unsigned int)max_groups * (unsigned int)B;
     if (identity) {
         hipExtLaunchKernelGGL(prefill_kernel<true>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(true), stream, ev.start,
                               ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc),
                               static_cast<const _Float16 *>(vt), static_cast<const int32_t *>(nullptr),
                               static_cast<const int32_t *>(nullptr), static_cast<const int32_t *>(nullptr), H, k, Tq,
-                              q_start, Tc_cap, Tp, n_qt, max_groups, scale, out);
+                              q_start, Tc_cap, Tp, n_qt_arg, max_groups, scale, out);
         return (int)hipGetLastError();
     }
     prefill_plan_kernel<<<dim3(B), 256, (size_t)(H + 2 * k) * sizeof(int32_t), stream>>>(h2c, rep, H, k, kGroup, max_groups,
@@ -518,7 +542,7 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     hipExtLaunchKernelGGL(prefill_kernel<false>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(false), stream, ev.start,
                           ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc),
                           static_cast<const _Float16 *>(vt), rep, static_cast<const int32_t *>(groups),
-                          static_cast<const int32_t *>(n_groups), H, k, Tq, q_start, Tc_cap, Tp, n_qt, max_groups, scale,
+                          static_cast<const int32_t *>(n_groups), H, k, Tq, q_start, Tc_cap, Tp, n_qt_arg, max_groups, scale,
                           out);
     return (int)hipGetLastError();
 }
