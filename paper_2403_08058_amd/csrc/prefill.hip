@@ -34,9 +34,6 @@ constexpr int kPWaves = 8;         // waves per workgroup (two per SIMD: one's M
 constexpr int kPBlock = kPWaves * 64;
 constexpr int kQTile = kQWave * kPWaves;   // 256 query rows per workgroup
 constexpr int kKTile = 64;         // keys per tile
-constexpr int kStagePieces = kKTile * kHeadDim * 2 / 16 / kPBlock;   // 16-byte pieces of one tile per thread
-constexpr int kKStride = kHeadDim + 8;     // halves per K row in LDS (272 B: rows land on different banks)
-constexpr int kVStride = kKTile + 8;       // halves per V^T row in LDS (144 B)
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kRescaleSlack = 8.0f;      // log2 units a tile may exceed the running maximum before a rescale
 
@@ -165,8 +162,8 @@ __global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t *__rest
 // tile t is read: ONE barrier per 64-key tile.
 // ---------------------------------------------------------------------------------------------------------
 constexpr int kKBufs = 3, kVBufs = 2;
-constexpr size_t kKBufBytes = (size_t)kKTile * kKStride * 2;
-constexpr size_t kVBufBytes = (size_t)kHeadDim * kVStride * 2;      // one member
+constexpr size_t kKBufBytes = (size_t)kKTile * kHeadDim * 2;        // 64 rows of 256 B (16 pieces), swizzled
+constexpr size_t kVBufBytes = (size_t)kHeadDim * kKTile * 2;        // one member: 128 rows of 128 B (8 pieces), swizzled
 constexpr size_t prefill_lds_bytes(bool ident) { return kKBufs * kKBufBytes + kVBufs * (ident ? 1 : kGroup) * kVBufBytes; }
 
 template <bool IDENT>
@@ -179,9 +176,9 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
                                                           float scale, float *__restrict__ out)
 {
     constexpr int G = IDENT ? 1 : kGroup;
-    extern __shared__ __attribute__((aligned(16))) char lds_raw[];
-    char *const k_lds = lds_raw;                                   // [kKBufs][kKTile][kKStride] bf16
-    char *const v_lds = lds_raw + kKBufs * kKBufBytes;             // [kVBufs][G][kHeadDim][kVStride] fp16
+    extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
+    char *const k_lds = lds_raw;                                   // [kKBufs][kKTile][128] bf16, swizzled rows
+    char *const v_lds = lds_raw + kKBufs * kKBufBytes;             // [kVBufs][G][kHeadDim][kKTile] fp16, swizzled rows
 
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int r = lane & 31, hl = lane >> 5;
@@ -240,43 +237,55 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         for (int ks = 0; ks < kHeadDim / 16; ++ks) qf[ks].raw = *reinterpret_cast<const u32x4 *>(qrow + ks * 32);
     }
 
-    // global -> registers -> LDS staging: a K tile is 1024 pieces of 16 bytes, a V^T tile of one head 128 rows x 8
-    // pieces (kStagePieces per thread each).  A tile sits in registers for one iteration before it is written.
+    // Staging with direct global -> LDS loads: one instruction moves 64 pieces of 16 bytes into 1 KB of consecutive
+    // LDS (lane l's piece lands at base + 16 l), no registers and no LDS write instructions.  Rows are therefore
+    // unpadded, and bank conflicts of the fragment reads are avoided by a swizzle instead: piece c of K row R sits
+    // in slot c ^ (R & 15) of the row, piece c of V^T row R in slot c ^ ((R >> 1) & 7); 16 consecutive rows read at
+    // one piece index then touch 16 different 16-byte slots of the 256-byte bank window.  A lane fetches whichever
+    // piece belongs in the slot it fills.  Wave w fills K rows 4w..4w+3 and 32+4w.. (two instructions per tile)
+    // and V^T rows 8w..8w+7 and 64+8w.. of every member (two instructions per member and tile).
     const char *ksrc = kc + ((size_t)b * k + cluster) * (size_t)Tc_cap * (kHeadDim * 2);
-    const _Float16 *vsrc[G];
+    const char *vsrc[G];
 #pragma unroll
-    for (int g = 0; g < G; ++g) vsrc[g] = vt + ((size_t)b * H + heads[g]) * (size_t)kHeadDim * Tp;
-    u32x4 kreg[kStagePieces], vreg[kStagePieces];      // the loop's staging registers; vreg: one member's V^T tile at a time
-    typedef u32x4 Pieces[kStagePieces];
-    auto fetch_k = [&](int kt, Pieces &regs) {
+    for (int g = 0; g < G; ++g)
+        vsrc[g] = reinterpret_cast<const char *>(vt + ((size_t)b * H + heads[g]) * (size_t)kHeadDim * Tp);
+    const int k_row = 4 * w + (lane >> 4), k_piece = (lane & 15) ^ (k_row & 15);
+    const int v_row = 8 * w + (lane >> 3), v_piece = (lane & 7) ^ ((v_row >> 1) & 7);
+    // V^T in memory: blocks of 32 keys, [block][row][32 keys]; piece c of a 64-key row = block c/4, 16 B piece c%4
+    const unsigned int v_off = (unsigned int)(((v_piece >> 2) * kHeadDim + v_row) * 64 + (v_piece & 3) * 16);
+    // (the instruction exists only in the device pass of the compiler; the host pass sees an empty body)
+    auto load_to_lds = [](const char *src, char *dst) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
+#else
+        (void)src;
+        (void)dst;
+#endif
+    };
+    auto dma_k = [&](int kt, int buf) {
         const int key0 = kt * kKTile;
 #pragma unroll
-        for (int i = 0; i < kStagePieces; ++i) {
-            const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
-            regs[i] = *reinterpret_cast<const u32x4 *>(ksrc + (size_t)min(key0 + row, n_keys - 1) * (kHeadDim * 2) + c * 16);
-        }
+        for (int i = 0; i < 2; ++i)
+            load_to_lds(ksrc + ((size_t)min(key0 + k_row + 32 * i, n_keys - 1) * (kHeadDim * 2) + k_piece * 16),
+                        k_lds + buf * kKBufBytes + (w + 8 * i) * 1024);
     };
-    auto fetch_v = [&](int kt, int g, Pieces &regs) {
+    auto dma_v = [&](int kt, int g, int buf) {
 #pragma unroll
-        for (int i = 0; i < kStagePieces; ++i) {
-            const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
-            regs[i] = *reinterpret_cast<const u32x4 *>(vsrc[g] + ((size_t)(2 * kt + (c >> 2)) * kHeadDim + dd) * 32 + (c & 3) * 8);
-        }
+        for (int i = 0; i < 2; ++i)
+            load_to_lds(vsrc[g] + ((size_t)kt * (2 * kHeadDim * 64) + v_off + i * 64 * 64),
+                        v_lds + (buf * G + g) * kVBufBytes + (w + 8 * i) * 1024);
     };
-    auto stage_k = [&](int buf, const Pieces &regs) {
-#pragma unroll
-        for (int i = 0; i < kStagePieces; ++i) {
-            const int piece = tid + i * kPBlock, row = piece >> 4, c = piece & 15;
-            *reinterpret_cast<u32x4 *>(k_lds + buf * kKBufBytes + (row * kKStride + c * 8) * 2) = regs[i];
-        }
+    // The barrier of the tile loop: every wave first waits for its own requests (the compiler does not track loads
+    // that land in LDS), then a bare s_barrier -- __syncthreads() would add fences the loads-to-LDS do not need.
+    auto tile_barrier = [&]() {
+#if defined(__HIP_DEVICE_COMPILE__)
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+#endif
     };
-    auto stage_v = [&](int buf, int g, const Pieces &regs) {
-#pragma unroll
-        for (int i = 0; i < kStagePieces; ++i) {
-            const int piece = tid + i * kPBlock, dd = piece >> 3, c = piece & 7;
-            *reinterpret_cast<u32x4 *>(v_lds + (buf * G + g) * kVBufBytes + (dd * kVStride + c * 8) * 2) = regs[i];
-        }
-    };
+    // fragment read offsets: this lane's row r of a 32-row block, piece index p -> byte offset inside the block
+    const int k_sw = r & 15, v_sw = (r >> 1) & 7;
 
     f32x16 acc[G][kHeadDim / 32];
 #pragma unroll
@@ -292,11 +301,11 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         f32x16 st;
 #pragma unroll
         for (int e = 0; e < 16; ++e) st[e] = 0.f;
-        const char *kb = k_lds + buf * kKBufBytes + ((half * 32 + r) * kKStride + hl * 8) * 2;
+        const char *kb = k_lds + buf * kKBufBytes + (half * 32 + r) * (kHeadDim * 2);
 #pragma unroll
         for (int ks = 0; ks < kHeadDim / 16; ++ks) {
             Frag16 kf;
-            kf.raw = *reinterpret_cast<const u32x4 *>(kb + ks * 32);
+            kf.raw = *reinterpret_cast<const u32x4 *>(kb + (((2 * ks + hl) ^ k_sw) << 4));
             st = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.bf, qf[ks].bf, st, 0, 0, 0);
         }
         return st;
@@ -353,13 +362,14 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
             // into "all MFMAs, then all exponentials", which would leave the matrix pipe idle during the latter.
 #pragma unroll
             for (int e = 0; e < 16; ++e) s_next[e] = 0.f;
-            const char *kb = k_lds + nbuf * kKBufBytes + ((nhalf * 32 + r) * kKStride + hl * 8) * 2;
+            const char *kb = k_lds + nbuf * kKBufBytes + (nhalf * 32 + r) * (kHeadDim * 2);
             Frag16 kf[kHeadDim / 16];
-            kf[0].raw = *reinterpret_cast<const u32x4 *>(kb);
-            kf[1].raw = *reinterpret_cast<const u32x4 *>(kb + 32);
+            kf[0].raw = *reinterpret_cast<const u32x4 *>(kb + ((hl ^ k_sw) << 4));
+            kf[1].raw = *reinterpret_cast<const u32x4 *>(kb + (((2 + hl) ^ k_sw) << 4));
 #pragma unroll
             for (int i = 0; i < kHeadDim / 16; ++i) {
-                if (i + 2 < kHeadDim / 16) kf[i + 2].raw = *reinterpret_cast<const u32x4 *>(kb + (i + 2) * 32);
+                if (i + 2 < kHeadDim / 16)
+                    kf[i + 2].raw = *reinterpret_cast<const u32x4 *>(kb + (((2 * (i + 2) + hl) ^ k_sw) << 4));
                 s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[i].bf, qf[i].bf, s_next, 0, 0, 0);
 #pragma unroll
                 for (int e = 2 * i; e < 2 * i + 2; ++e) {
@@ -385,19 +395,21 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             if (g < n_mem) {
-                const char *vb = v_lds + (vbuf * G + g) * kVBufBytes + (r * kVStride + half * 32 + 8 * hl) * 2;
+                const char *vb = v_lds + (vbuf * G + g) * kVBufBytes + r * (kKTile * 2);
                 constexpr int kBlks = kHeadDim / 32, kFrags = 2 * kBlks, kVAhead = 3;
-                // fragment j: value rows 32 * (j % kBlks) .., keys 16 * (j / kBlks) .. of the block; the two MFMAs
-                // that add into the same accumulator are kBlks apart
+                // fragment j: value rows 32 * (j % kBlks) .., keys 16 * (j / kBlks) .. of the block (piece
+                // 4 * half + 2 * (j / kBlks) + hl of the row); the two MFMAs that add into the same accumulator are
+                // kBlks apart
+                auto v_frag = [&](int j) {
+                    return *reinterpret_cast<const u32x4 *>(vb + (j % kBlks) * 32 * (kKTile * 2) +
+                                                            (((4 * half + 2 * (j / kBlks) + hl) ^ v_sw) << 4));
+                };
                 Frag16 vf[kFrags];
 #pragma unroll
-                for (int j = 0; j < kVAhead; ++j)
-                    vf[j].raw = *reinterpret_cast<const u32x4 *>(vb + ((j % kBlks) * 32 * kVStride + 16 * (j / kBlks)) * 2);
+                for (int j = 0; j < kVAhead; ++j) vf[j].raw = v_frag(j);
 #pragma unroll
                 for (int j = 0; j < kFrags; ++j) {
-                    if (j + kVAhead < kFrags)
-                        vf[j + kVAhead].raw = *reinterpret_cast<const u32x4 *>(
-                            vb + (((j + kVAhead) % kBlks) * 32 * kVStride + 16 * ((j + kVAhead) / kBlks)) * 2);
+                    if (j + kVAhead < kFrags) vf[j + kVAhead].raw = v_frag(j + kVAhead);
                     acc[g][j % kBlks] =
                         __builtin_amdgcn_mfma_f32_32x32x16_f16(vf[j].h, pf[j / kBlks].h, acc[g][j % kBlks], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
@@ -409,56 +421,36 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     const std::true_type with_next;
     const std::false_type last_block;
 
-    // prologue: K(0), K(1), V(0) into LDS, K(2) and the first member's V(1) into the loop's registers.  All requests
-    // go out before the first is waited for: the workgroup is alone on its CU, nothing else hides this latency.
-    {
-        Pieces k0, k1, v00, v01;
-        const bool two = G > 1 && n_mem > 1;
-        fetch_k(0, k0);
-        fetch_v(0, 0, v00);
-        if (two) fetch_v(0, 1, v01);
-        if (n_tiles > 1) fetch_k(1, k1);
-        if (n_tiles > 2) fetch_k(2, kreg);
-        if (n_tiles > 1) fetch_v(1, 0, vreg);
-        stage_k(0, k0);
-        stage_v(0, 0, v00);
-        if (two) stage_v(0, 1, v01);
-        if (n_tiles > 1) stage_k(1, k1);
-    }
-    __syncthreads();
-    // every wave, padding waves included: the first use of the query fragments is then outside the loop, and the
-    // loop body never has to wait for the loads that filled them (nor, in their shadow, for the prefetches)
+    // prologue: K(0), K(1), V(0) requested together; the previous pass's last barrier has freed every buffer
+    dma_k(0, 0);
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        if (g < n_mem) dma_v(0, g, 0);
+    if (n_tiles > 1) dma_k(1, 1);
+    tile_barrier();
+    // every wave, padding waves included: the first use of the query fragments is then outside the loop
     f32x16 s_cur = score_block(0, 0);
 
-    // Staging schedule of iteration kt (tile kt is computed): at the top K(kt+2) and the first member's V(kt+1) go
-    // from registers to LDS and K(kt+3) and the second member's V(kt+1) are requested; between the two blocks of
-    // the tile the second member's V(kt+1) is written and the first member's V(kt+2) requested.  One member's tile
-    // in registers at a time keeps the register count of two-member groups inside the budget.
+    // Iteration kt computes tile kt while K(kt+2) and V(kt+1) stream into the buffers that tile kt-1 has left
+    // (its readers passed the barrier that ended iteration kt-1); they must have landed by the barrier that ends
+    // this iteration.
     int kb3 = 0, vb2 = 0;                      // kt % 3, kt % 2
     for (int kt = 0; kt < n_tiles; ++kt) {
         const int kb3_1 = kb3 == 2 ? 0 : kb3 + 1, kb3_2 = kb3_1 == 2 ? 0 : kb3_1 + 1;
-        const bool more = kt + 1 < n_tiles;
-        if (kt + 2 < n_tiles) stage_k(kb3_2, kreg);
-        if (more) stage_v(vb2 ^ 1, 0, vreg);
-        if (kt + 3 < n_tiles) fetch_k(kt + 3, kreg);
-        if (G > 1 && n_mem > 1) {
-            if (more) fetch_v(kt + 1, 1, vreg);
-        } else if (kt + 2 < n_tiles) {
-            fetch_v(kt + 2, 0, vreg);
+        if (kt + 2 < n_tiles) dma_k(kt + 2, kb3_2);
+        if (kt + 1 < n_tiles) {
+#pragma unroll
+            for (int g = 0; g < G; ++g)
+                if (g < n_mem) dma_v(kt + 1, g, vb2 ^ 1);
         }
+        __builtin_amdgcn_sched_barrier(0);
 
         const int hb = 2 * kt;                             // blocks hb (first half of the tile) and hb + 1
         if (hb + 1 < n_hb) s_cur = block(s_cur, hb * 32, vb2, 0, with_next, kb3, 1);
         else if (hb < n_hb) s_cur = block(s_cur, hb * 32, vb2, 0, last_block, 0, 0);
-
-        if (G > 1 && n_mem > 1) {
-            if (more) stage_v(vb2 ^ 1, 1, vreg);
-            if (kt + 2 < n_tiles) fetch_v(kt + 2, 0, vreg);
-        }
-
         if (hb + 2 < n_hb) s_cur = block(s_cur, hb * 32 + 32, vb2, 1, with_next, kb3_1, 0);
         else if (hb + 1 < n_hb) s_cur = block(s_cur, hb * 32 + 32, vb2, 1, last_block, 0, 0);
-        __syncthreads();                                   // tile kt is done with; tiles kt+1 / kt+2 are visible
+        tile_barrier();                                    // tile kt is done with; tiles kt+1 / kt+2 are in LDS
         kb3 = kb3_1;
         vb2 ^= 1;
     }
