@@ -168,9 +168,9 @@ def phase_timing(layers, cfg, ws, C, torch, steps):
     return {li: (s / steps, v / steps) for li, (s, v) in per_layer.items()}
 
 
-def read_traffic(cfg_name):
-    """HBM bytes per value-kernel launch from the committed rocprofv3 counter summary, if there is one."""
-    path = os.path.join(ROOT, "profiles", f"value_kernel_{cfg_name}_hbm_traffic.txt")
+def read_traffic(cfg_name, kernel="value_kernel"):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if there is one."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{cfg_name}_hbm_traffic.txt")
     try:
         m = re.search(r"^traffic_bytes_per_launch:\s*([0-9.eE+]+)", open(path).read(), re.M)
         return float(m.group(1)) if m else None
@@ -294,7 +294,8 @@ def prefill_main(args, cfg, torch, C, W):
         kms = sum(kern[k_dom]) / len(kern[k_dom])
         ach = layer_flops[k_dom] / (kms * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": f"prefill_kernel, layers with {k_dom} clusters", "achieved": ach,
-                "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0, "traffic": None,
+                "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0,
+                "traffic": read_traffic(cfg.name, "prefill_kernel") if T == W.CONFIGS[cfg.name].T else None,
                 "avg_launch_ms": kms, "flops_per_launch": layer_flops[k_dom],
                 "kernel_ms_by_clusters": {str(k): sum(v) / len(v) for k, v in sorted(kern.items())}}
     else:
@@ -499,7 +500,8 @@ def project_main(args, cfg, torch, C, W):
                                f"{sorted(set(ks_all))}, {n_res} layers resident and visited in turn",
                    "layers": cfg.L, "heads": H, "head_dim": d, "batch": B, "prompt": T},
         "roofline": {"bound": "mfma", "kernel": f"project_kernel, layers with {k_dom} clusters", "achieved": ach,
-                     "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0, "traffic": None,
+                     "peak": 2500.0, "unit": "TFLOP/s", "frac": ach / 2500.0,
+                     "traffic": read_traffic(cfg.name, "project_kernel") if T == W.CONFIGS[cfg.name].T else None,
                      "avg_launch_ms": kern[k_dom], "flops_per_launch": layer_flops[k_dom],
                      "kernel_ms_by_clusters": {str(k): v for k, v in sorted(kern.items())}},
         "TFLOPs_whole_step": flops / (ms * 1e-3) / 1e12,
