@@ -632,7 +632,8 @@ def main():
         s_ms = sum(s for s, _ in ph.values()) / len(ph)
         ach = v_bytes / (v_ms * 1e-3) / 1e9
         result["roofline"] = {"bound": "hbm", "kernel": "value_kernel", "achieved": ach, "peak": HBM_PEAK_GBS,
-                              "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": read_traffic(cfg.name),
+                              "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                              "traffic": read_traffic(cfg.name) if T == W.CONFIGS[cfg.name].T else None,
                               "bytes_per_launch": v_bytes, "avg_launch_ms": v_ms}
         result["score_kernel"] = {"avg_launch_ms": s_ms, "avg_bytes_per_launch": s_bytes,
                                   "achieved_GBps": s_bytes / (s_ms * 1e-3) / 1e9}
