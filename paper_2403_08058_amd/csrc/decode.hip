@@ -126,13 +126,12 @@ __device__ __forceinline__ int batch_row(int it, int w, int u, int rg)
 // so that growing the cache costs no launch of its own.
 // ---------------------------------------------------------------------------------------------------------
 template <bool BF16, bool IDENT, bool APPEND>
-__global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ q, const char *__restrict__ kc_in,
+__global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ q, const char *__restrict__ kc,
                                                        const int32_t *__restrict__ rep, int H, int k, int T,
                                                        int Tc_cap, float scale, int cs, int n_cs,
                                                        float *__restrict__ scores, float2 *__restrict__ stats,
                                                        const char *__restrict__ k_new)
 {
-    const char *const kc = kc_in;
     using TL = Tile<BF16>;
     __shared__ float s_lds[kMaxCs];
     __shared__ float red[kWaves];
