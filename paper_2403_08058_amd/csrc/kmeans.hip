@@ -62,7 +62,8 @@ __global__ __launch_bounds__(64) void feature_kernel(const void *__restrict__ q5
 
 // ---------------------------------------------------------------------------------------------------------
 // K-Means: grid (B), one workgroup of 256 threads per batch row.  Dynamic LDS: centres [k][F] fp64, per-head
-// distance [H] fp64, slice winners [H][slices], assignment/previous assignment [H], counts/labels [k].
+// distance [H] fp64, slice winners [H][slices], assignment/previous assignment/member order [H],
+// counts/labels/list starts [k], and a copy of the features when it fits.
 // ---------------------------------------------------------------------------------------------------------
 __device__ __forceinline__ double sqdist(const float *__restrict__ x, const double *c, int F)
 {
@@ -77,7 +78,7 @@ __device__ __forceinline__ double sqdist(const float *__restrict__ x, const doub
 
 __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict__ feat, int H, int F, int k,
                                                         const int32_t *__restrict__ init_heads, int max_iter,
-                                                        int slices, int32_t *__restrict__ h2c,
+                                                        int slices, int stage_x, int32_t *__restrict__ h2c,
                                                         int32_t *__restrict__ rep, int32_t *__restrict__ ncl,
                                                         int32_t *__restrict__ iters)
 {
@@ -90,15 +91,20 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
     int *prev = assign + H;                                 // [H]
     int *count = prev + H;                                  // [k]
     int *label = count + k;                                 // [k]
-    __shared__ int changed;
+    int *order = label + k;                                 // [H] heads sorted by centre, ascending inside a centre
+    int *first = order + H;                                 // [k] where a centre's heads start in `order`
+    float *x_lds = reinterpret_cast<float *>(first + k);    // [H][F] copy of the features, when it fits
 
     const int b = blockIdx.x, tid = threadIdx.x;
-    const float *X = feat + (size_t)b * H * F;
+    const float *Xg = feat + (size_t)b * H * F;
+    if (stage_x)
+        for (int i = tid; i < H * F; i += kBlock) x_lds[i] = Xg[i];
+    const float *X = stage_x ? x_lds : Xg;                  // same values either way
 
     for (int i = tid; i < k * F; i += kBlock) {
         const int j = i / F, f = i - j * F;
         const int h0 = min(max(init_heads[(size_t)b * k + j], 0), H - 1);
-        centre[i] = (double)X[(size_t)h0 * F + f];
+        centre[i] = (double)Xg[(size_t)h0 * F + f];
     }
     for (int h = tid; h < H; h += kBlock) prev[h] = -1;
     __syncthreads();
@@ -135,43 +141,63 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
             dmin[h] = bd;
         }
         __syncthreads();
-        if (tid == 0) {
-            for (int j = 0; j < k; ++j) count[j] = 0;
-            for (int h = 0; h < H; ++h) count[assign[h]]++;
-            // centres that received no head take, in ascending order, the farthest head of a cluster that can
-            // spare one
-            for (int j = 0; j < k; ++j) {
-                if (count[j] != 0) continue;
-                int pick = -1;
-                double far = 0.0;
-                for (int h = 0; h < H; ++h)
-                    if (count[assign[h]] >= 2 && dmin[h] > far) { far = dmin[h]; pick = h; }
-                if (pick < 0) continue;
-                count[assign[pick]]--;
-                assign[pick] = j;
-                count[j] = 1;
-                dmin[pick] = 0.0;
+        // members per centre: thread j counts centre j (integers: any order gives the sequential result)
+        int empty = 0;
+        for (int j = tid; j < k; j += kBlock) {
+            int n = 0;
+            for (int h = 0; h < H; ++h) n += assign[h] == j;
+            count[j] = n;
+            empty |= n == 0;
+        }
+        // Centres that received no head take, in ascending order, the farthest head of a cluster that can spare
+        // one.  Sequential by nature, but needed only when some centre is empty.
+        if (__syncthreads_or(empty)) {
+            if (tid == 0) {
+                for (int j = 0; j < k; ++j) {
+                    if (count[j] != 0) continue;
+                    int pick = -1;
+                    double far = 0.0;
+                    for (int h = 0; h < H; ++h)
+                        if (count[assign[h]] >= 2 && dmin[h] > far) { far = dmin[h]; pick = h; }
+                    if (pick < 0) continue;
+                    count[assign[pick]]--;
+                    assign[pick] = j;
+                    count[j] = 1;
+                    dmin[pick] = 0.0;
+                }
             }
-            int ch = 0;
-            for (int h = 0; h < H; ++h) {
-                if (assign[h] != prev[h]) ch = 1;
-                prev[h] = assign[h];
-            }
-            changed = ch;
+            __syncthreads();
+        }
+        int moved = 0;
+        for (int h = tid; h < H; h += kBlock) {
+            moved |= assign[h] != prev[h];
+            prev[h] = assign[h];
+        }
+        const int changed = __syncthreads_or(moved);        // same value in every thread
+        if (!changed || it >= max_iter) break;
+        // member lists: thread j writes the heads of centre j, in ascending order, behind those of the centres
+        // before it
+        for (int j = tid; j < k; j += kBlock) {
+            int at = 0;
+            for (int i = 0; i < j; ++i) at += count[i];
+            first[j] = at;
+            for (int h = 0; h < H; ++h)
+                if (assign[h] == j) order[at++] = h;
         }
         __syncthreads();
-        if (!changed || it >= max_iter) break;      // same value in every thread
         // update: one thread per (centre, coordinate), members added in head order
         for (int i = tid; i < k * F; i += kBlock) {
             const int j = i / F, f = i - j * F;
-            if (count[j] == 0) continue;
+            const int n = count[j];
+            if (n == 0) continue;
+            const int *mem = order + first[j];
             double acc = 0.0;
-            for (int h = 0; h < H; ++h)
-                if (assign[h] == j) acc = acc + (double)X[(size_t)h * F + f];
-            centre[i] = acc / (double)count[j];
+            for (int m = 0; m < n; ++m) acc = acc + (double)X[(size_t)mem[m] * F + f];
+            centre[i] = acc / (double)n;
         }
         __syncthreads();
     }
+    __syncthreads();
 
     // canonical labels: clusters numbered by their lowest member, which represents them
     if (tid == 0) {
@@ -274,14 +300,23 @@ int launch_score_features(const void *q5, const void *k5, int B, int H, int n_to
 size_t assign_clusters_lds_bytes(int H, int F, int k)
 {
     const size_t sl = (size_t)assignment_slices(H, k);
-    return sizeof(double) * ((size_t)k * F + H + H * sl) + sizeof(int) * (H * sl + 2 * (size_t)H + 2 * (size_t)k);
+    return sizeof(double) * ((size_t)k * F + H + H * sl) + sizeof(int) * (H * sl + 3 * (size_t)H + 3 * (size_t)k);
+}
+
+// the features are copied to LDS too when that still fits the 64 KB a workgroup may ask for
+constexpr size_t kKmeansLdsLimit = 64 * 1024 - 64;
+size_t kmeans_feature_copy_bytes(int H, int F, int k)
+{
+    const size_t extra = sizeof(float) * (size_t)H * F;
+    return assign_clusters_lds_bytes(H, F, k) + extra <= kKmeansLdsLimit ? extra : 0;
 }
 
 int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const int32_t *init_heads, int max_iter,
                            int32_t *h2c, int32_t *rep, int32_t *ncl, int32_t *iters, hipStream_t stream)
 {
-    kmeans_kernel<<<dim3(B), kBlock, assign_clusters_lds_bytes(H, F, k), stream>>>(
-        feat, H, F, k, init_heads, max_iter, assignment_slices(H, k), h2c, rep, ncl, iters);
+    const size_t copy = kmeans_feature_copy_bytes(H, F, k);
+    kmeans_kernel<<<dim3(B), kBlock, assign_clusters_lds_bytes(H, F, k) + copy, stream>>>(
+        feat, H, F, k, init_heads, max_iter, assignment_slices(H, k), copy != 0 ? 1 : 0, h2c, rep, ncl, iters);
     return (int)hipGetLastError();
 }
 
