@@ -19,6 +19,7 @@ struct DecodePlan {
     int n_cs;        // score chunks per (b, cluster) = ceil(T / cs)
     int cp;          // tokens per workgroup of the value kernel
     int n_cp;        // value chunks per (b, head) = ceil(T / cp)
+    int ds;          // workgroups per (b, head, chunk) of the value kernel: 1, or 2 with half of the columns each
     size_t off_scores, off_stats, off_partial, off_rows, bytes;   // off_rows: [B,H,128] fp32 staging rows
 };
 

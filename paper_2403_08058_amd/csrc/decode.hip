@@ -31,6 +31,18 @@ struct Tile {
     static constexpr int ROW_BYTES = kHeadDim * (BF16 ? 2 : 4);
 };
 
+// Value kernel: a workgroup may take only one of DS column parts of its head's rows (DS = 1: whole rows).
+template <bool BF16, int DS>
+struct VTile {
+    static constexpr int EPL = BF16 ? 8 : 4;
+    static constexpr int COLS = kHeadDim / DS;             // columns of this workgroup
+    static constexpr int LPR = COLS / EPL;                 // lanes per (part of a) row
+    static constexpr int RPW = 64 / LPR;                   // rows per wave load
+    static constexpr int BATCH = RPW * kUnroll;            // rows per wave batch (at most 64)
+    static constexpr int ROW_BYTES = kHeadDim * (BF16 ? 2 : 4);
+    static constexpr int PART_BYTES = ROW_BYTES / DS;
+};
+
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ void unpack(const u32x4 &raw, float (&f)[8])
@@ -227,7 +239,10 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
 // ---------------------------------------------------------------------------------------------------------
 // APPEND: position T-1 is the token being decoded; the workgroup whose chunk ends there takes its value row from
 // v_new [B,H,d], weighs it like any other row and writes it to the cache.
-template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND>
+// DS = 2: two workgroups per head, each with half of the columns of every row (128-byte pieces, whole cache
+// lines): twice the workgroups without partial rows to add up afterwards -- for head counts that are too small
+// for one workgroup per head and would otherwise pay a combine launch.  grid = (n_cp, H * DS, B).
+template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND, int DS>
 __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__ v,
                                                         const int32_t *__restrict__ h2c,
                                                         const int32_t *__restrict__ rep, int H, int k, int T,
@@ -238,14 +253,14 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
                                                         float *__restrict__ probs_out,
                                                         const char *__restrict__ v_new)
 {
-    using TL = Tile<BF16>;
+    using TL = VTile<BF16, DS>;
     __shared__ float p_lds[NW][TL::BATCH];
-    __shared__ float acc_lds[NW][kHeadDim];
+    __shared__ float acc_lds[NW][TL::COLS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
     const int cg = lane % TL::LPR, rg = lane / TL::LPR;
-    const int split = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int split = blockIdx.x, h = blockIdx.y / DS, dpart = blockIdx.y % DS, b = blockIdx.z;
     const int t0 = split * cp;
     const int n_all = min(T, t0 + cp) - t0;
     const bool has_new = APPEND && split == n_cp - 1;        // this chunk ends with the token being decoded
@@ -255,7 +270,7 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
 
     // uniform base of the chunk + a 32-bit per-lane byte offset (a chunk is far below 4 GiB)
     const char *vbase = v + (((size_t)b * H + h) * T_cap + t0) * TL::ROW_BYTES;
-    const unsigned int lane_off = cg * 16;
+    const unsigned int lane_off = dpart * TL::PART_BYTES + cg * 16;
 
     // one batch: the 16-byte pieces of kUnroll * RPW consecutive rows, and (lanes < BATCH) one row's score
     struct Batch {
@@ -283,7 +298,7 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     const size_t crow = (size_t)b * k + c;
     const float *srow = scores + crow * T + t0;
     float *prow = nullptr;
-    if (WRITE_P) prow = (probs_out != nullptr && (IDENT || rep[crow] == h)) ? probs_out + crow * T + t0 : nullptr;
+    if (WRITE_P) prow = (probs_out != nullptr && dpart == 0 && (IDENT || rep[crow] == h)) ? probs_out + crow * T + t0 : nullptr;
 
     // the score this lane turns into a probability for batch `it` (lanes >= BATCH and rows past the end: none;
     // they still issue the load, of the last score, to keep the count fixed)
@@ -357,21 +372,22 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     // lane groups of a wave, then the waves
 #pragma unroll
     for (int e = 0; e < TL::EPL; ++e) {
-        if (BF16) acc[e] += __shfl_xor(acc[e], 16);
-        acc[e] += __shfl_xor(acc[e], 32);
+#pragma unroll
+        for (int o = TL::LPR; o < 64; o <<= 1) acc[e] += __shfl_xor(acc[e], o);
     }
     if (rg == 0) {
 #pragma unroll
         for (int e = 0; e < TL::EPL; ++e) acc_lds[w][cg * TL::EPL + e] = acc[e];
     }
     __syncthreads();
-    if (tid < kHeadDim) {
+    if (tid < TL::COLS) {
         float val = 0.f;
 #pragma unroll
         for (int i = 0; i < NW; ++i) val += acc_lds[i][tid];
         const size_t orow = (size_t)b * H + h;
-        if (n_cp == 1) out[orow * kHeadDim + tid] = val;
-        else partial[(orow * n_cp + split) * kHeadDim + tid] = val;     // combine_kernel adds the rows up
+        const int col = dpart * TL::COLS + tid;
+        if (n_cp == 1) out[orow * kHeadDim + col] = val;
+        else partial[(orow * n_cp + split) * kHeadDim + col] = val;     // combine_kernel adds the rows up
     }
 }
 
@@ -436,7 +452,7 @@ int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H
 // arrival counter) was measured and dropped: with __threadfence() in every workgroup the kernel ran 10x slower
 // (L2 write-back + invalidate per fence across 8 XCDs), and with fence-free device-scope stores/loads it was
 // still slower than the separate combine launch at every chunk count tried.
-template <bool BF16, bool IDENT, int NW, int NB>
+template <bool BF16, bool IDENT, int NW, int NB, int DS>
 int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
                   hipStream_t stream, const MemberRows *members, const void *v_new)
@@ -445,18 +461,18 @@ int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
     // production kernel has no store inside its streaming loop; so does the variant that appends the new token
     const char *no_new = nullptr;
     if (!IDENT && v_new != nullptr)
-        hipExtLaunchKernelGGL((value_kernel<BF16, false, NW, NB, false, true>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0,
+        hipExtLaunchKernelGGL((value_kernel<BF16, false, NW, NB, false, true, DS>), dim3(pl.n_cp, H * DS, B), dim3(NW * 64), 0,
                               stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
                               pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
                               static_cast<const float2 *>(w.stats), w.partial, out, probs_out,
                               static_cast<const char *>(v_new));
     else if (probs_out != nullptr)
-        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, true, false>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0,
+        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, true, false, DS>), dim3(pl.n_cp, H * DS, B), dim3(NW * 64), 0,
                               stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
                               pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
                               static_cast<const float2 *>(w.stats), w.partial, out, probs_out, no_new);
     else
-        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, false, false>), dim3(pl.n_cp, H, B), dim3(NW * 64), 0,
+        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, false, false, DS>), dim3(pl.n_cp, H * DS, B), dim3(NW * 64), 0,
                               stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
                               pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
                               static_cast<const float2 *>(w.stats), w.partial, out, probs_out, no_new);
@@ -488,13 +504,18 @@ int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, i
     if (getenv("CHAI_NW")) nw = atoi(getenv("CHAI_NW"));
     if (getenv("CHAI_NB")) nb = atoi(getenv("CHAI_NB"));
     if (nw == 4 && nb == 3)
-        return values_launch<BF16, IDENT, 4, 3>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+        return values_launch<BF16, IDENT, 4, 3, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
     if (nw == 16 && nb == 1)
-        return values_launch<BF16, IDENT, 16, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+        return values_launch<BF16, IDENT, 16, 1, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
 #endif
+    if (pl.ds == 2) {
+        if (nw == 4 && nb == 2)
+            return values_launch<BF16, IDENT, 4, 2, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+        return values_launch<BF16, IDENT, 8, 1, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+    }
     if (nw == 4 && nb == 2)
-        return values_launch<BF16, IDENT, 4, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
-    return values_launch<BF16, IDENT, 8, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+        return values_launch<BF16, IDENT, 4, 2, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+    return values_launch<BF16, IDENT, 8, 1, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
@@ -511,11 +532,17 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
     }
     // value chunk (measured on MI355X at T = 2048): with >= 384 heads one workgroup per head -- whole row of
     // the cache, no partial rows, no combine launch -- is fastest (416 heads: 39 us against 41-44 us split);
-    // with fewer heads the single workgroups become latency-bound and splitting into >= 1024 workgroups wins
-    // even with the extra launch (288 heads: 30 us with 4 chunks against 34 us unsplit).
+    // with fewer heads the single workgroups become latency-bound and the tokens are split into >= 1024
+    // workgroups whose partial rows a combine launch adds up (288 heads: 30 us with 4 chunks against 34 us
+    // unsplit).  Between 192 and 383 heads and up to 1536 tokens, two workgroups per head that take half of the
+    // columns each do better still: enough workgroups without partial rows and without the combine launch
+    // (288 heads: 18.6 against 21.7 us at 640 tokens, 23.0 against 24.3 at 1024, 30.3 against 30.8 at 1536; at
+    // 2048 the token split is 3 % ahead again).
     {
         const long long heads = (long long)B * H > 0 ? (long long)B * H : 1;
-        long long want = heads >= 384 ? 1 : (1024 + heads - 1) / heads;
+        pl.ds = (heads >= 192 && heads < 384 && T <= 1536) ? 2 : 1;
+        const long long groups = heads * pl.ds;
+        long long want = groups >= 384 ? 1 : (1024 + groups - 1) / groups;
         const long long most = (T + 127) / 128;
         if (want > most) want = most;
         pl.cp = (int)(((T + want - 1) / want + 127) / 128 * 128);
@@ -524,6 +551,7 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
     // experiment hooks, compiled only into tuning builds
     if (const char *e = getenv("CHAI_CS")) pl.cs = atoi(e);
     if (const char *e = getenv("CHAI_CP")) pl.cp = atoi(e);
+    if (const char *e = getenv("CHAI_DS")) pl.ds = atoi(e);
 #endif
     pl.n_cs = (T + pl.cs - 1) / pl.cs;
     pl.n_cp = (T + pl.cp - 1) / pl.cp;

@@ -159,6 +159,8 @@ def test_members_with_identical_qk_equal_dense():
     (5, 32, 4, 1025, 1100),     # chunk boundary + 1
     (1, 1, 1, 33, 40),          # one head
     (2, 32, 8, 16, 16),         # exactly one load group (bf16) / two (fp32)
+    (4, 72, 16, 1300, 1333),    # 288 heads: two workgroups per head, half of the columns each
+    (6, 32, 8, 77, 80),         # 192 heads, short context
 ])
 def test_decode_edge_shapes(dtype, B, H, kk, T, T_cap):
     cfg = W.Config("edge", L=1, H=H, d=128, B=B, T=T, T_cap=T_cap, dtype=dtype, ks=(kk,), membership="random",
