@@ -19,9 +19,13 @@
  * the shared-value ablation against dense attention of the representative,
  * the nearest-to-mean representative against hand-worked cases and numpy,
  * the representatives' projections against a library contraction.
- * Unpinned: nothing in this file.  (How well clustered attention
- * approximates dense attention on trained models is not computed here at
- * all; it needs weights and datasets.)
+ * Unpinned: no function of this file.  One clause inside chai_oracle_kmeans
+ * is a safeguard that no example separates from its relaxation: an empty
+ * centre takes a head only from a cluster that holds at least two ("at least
+ * one" gave the same partitions on 500 000 random small problems), so that
+ * clause is parity unpinned as a rule on its own.  (How well clustered
+ * attention approximates dense attention on trained models is not computed
+ * here at all; it needs weights and datasets.)
  *
  * All pointers are HOST pointers.  dtype: 0 = fp32, 1 = bf16 (raw uint16
  * bit patterns, converted exactly by placing them in the top half of an
