@@ -424,3 +424,23 @@ def test_argument_errors():
     feat = torch.zeros((1, 300, 4), dtype=torch.float32, device="cuda")
     init = torch.zeros((1, 2), dtype=torch.int32, device="cuda")
     assert status(C.chai_assign_clusters, feat, init) == 5                                        # H > 256
+
+
+def _random_shapes(n, seed):
+    """Seeded draw of decode shapes around the planner's thresholds (192 / 384 heads, 1536 tokens, chunk edges)."""
+    g = np.random.default_rng(seed)
+    out = []
+    for i in range(n):
+        H = int(g.choice([1, 3, 8, 32, 40, 52, 72]))
+        B = int(g.choice([1, 2, 3, 5, 6, 8, 12]))
+        kk = int(g.integers(1, H + 1)) if H < 8 else int(g.choice([1, 2, 4, 8]))
+        T = int(g.choice([1, 2, 31, 33, 64, 127, 129, 255, 257, 640, 1000, 1535, 1537, 2049]))
+        out.append((W.F32 if i % 3 == 0 else W.BF16, B, H, min(kk, H), T, T + int(g.integers(0, 9))))
+    return out
+
+
+@pytest.mark.parametrize("dtype,B,H,kk,T,T_cap", _random_shapes(24, 20240527))
+def test_decode_random_shapes(dtype, B, H, kk, T, T_cap):
+    cfg = W.Config("rand", L=1, H=H, d=128, B=B, T=T, T_cap=T_cap, dtype=dtype, ks=(kk,), membership="random",
+                   seed=B * 3 + H * 5 + kk * 11 + T)
+    G.run_clustered_layer(cfg, W.layer_inputs(cfg, 0))
