@@ -184,3 +184,21 @@ def test_prefill_full_size_sampled(name, T):
         assert ok, f"{name} (b={b}, h={h}, rows {i0}..): err/allowed {ratio:.3g}"
         worst = max(worst, ratio)
     print(f"worst err/allowed = {worst:.3f}")
+
+
+def _random_prefill_shapes(n, seed):
+    g = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        H = int(g.choice([2, 5, 8, 32, 52]))
+        B = int(g.choice([1, 2, 3]))
+        kk = int(g.integers(1, min(H, 16) + 1))
+        Tq = int(g.choice([1, 31, 33, 64, 65, 255, 257, 300, 513]))
+        q_start = int(g.choice([0, 1, 5, 63, 64, 200]))
+        out.append((B, H, kk, Tq, q_start, q_start + Tq + int(g.integers(0, 5))))
+    return out
+
+
+@pytest.mark.parametrize("B,H,kk,Tq,q_start,T_cap", _random_prefill_shapes(10, 77001))
+def test_prefill_random_shapes(B, H, kk, Tq, q_start, T_cap):
+    run_case(B, H, kk, Tq, q_start, T_cap, seed=B + 3 * H + 7 * kk + Tq + q_start)
