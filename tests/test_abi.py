@@ -134,3 +134,12 @@ def test_product_does_not_import_the_oracle():
         if f.endswith((".py", ".c", ".h")):
             text = open(os.path.join(ROOT, "oracle", f)).read()
             assert "paper_2403_08058_amd" not in text and "libchai.so" not in text
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """One GPU only: bench.py --gpus N with N > 1 exits with a message before touching any device."""
+    import subprocess
+    import sys
+    res = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                         timeout=120)
+    assert res.returncode == 2 and "ONE GPU" in res.stderr and res.stdout.strip() == ""
