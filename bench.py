@@ -168,6 +168,24 @@ def phase_timing(layers, cfg, ws, C, torch, steps):
     return {li: (s / steps, v / steps) for li, (s, v) in per_layer.items()}
 
 
+def read_ceiling(layers, C, torch):
+    """Rate of a bare streaming read (the library's probe kernel) over the resident value caches, one launch per
+    layer, timed with events stamped at each kernel's begin and end: the practical ceiling of the HBM-bound
+    kernels on this device."""
+    hev = HipEvents()
+    sink = torch.zeros((1,), dtype=torch.float32, device="cuda")
+    recs = []
+    for rep in range(3):
+        for L in layers[:16]:
+            e0, e1 = hev.create(), hev.create()
+            C.chai_stream_read_probe(L.v, sink, start_event=e0, stop_event=e1)
+            recs.append((rep, L.v.numel() * L.v.element_size(), e0, e1))
+    torch.cuda.synchronize()
+    rates = sorted(nb / (hev.elapsed_ms(e0, e1) * 1e-3) / 1e9 for rep, nb, e0, e1 in recs if rep > 0)
+    hev.close()
+    return rates[len(rates) // 2]
+
+
 def read_traffic(cfg_name, kernel="value_kernel"):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{cfg_name}_hbm_traffic.txt")
@@ -637,6 +655,11 @@ def main():
                               "bytes_per_launch": v_bytes, "avg_launch_ms": v_ms}
         result["score_kernel"] = {"avg_launch_ms": s_ms, "avg_bytes_per_launch": s_bytes,
                                   "achieved_GBps": s_bytes / (s_ms * 1e-3) / 1e9}
+        ceiling = read_ceiling(layers, C, torch)
+        result["read_ceiling"] = {"GBps": ceiling, "frac_of_peak": ceiling / HBM_PEAK_GBS,
+                                  "value_kernel_frac_of_ceiling": ach / ceiling,
+                                  "step_frac_of_ceiling": result["algorithmic_GBps"] / ceiling,
+                                  "how": "bare streaming read of the value caches (chai_stream_read_probe), median launch"}
 
     if not args.no_cpu_baseline:
         clustered_step()

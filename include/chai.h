@@ -413,6 +413,21 @@ int chai_project_qk_timed(const void *x, const void *w_q, const void *w_k, const
                           int k, int Tn, int D, int d, int dtype, void *q_out, void *k_compact, int pos0,
                           int Tc_cap, void *stream, void *start_event, void *stop_event);
 
+/*
+ * Measurement aid, not a step of the method: a bare streaming read of
+ * `bytes` bytes (a multiple of 16, 16-byte aligned) of device memory with the
+ * load pattern of the decode kernels (16-byte non-temporal loads, eight in
+ * flight per lane, 64-512 KiB per workgroup).  The rate it reaches is the
+ * practical ceiling for the HBM-bound kernels above on the device at hand;
+ * the benchmark quotes its kernels against it next to the nominal peak.
+ *   sink        one fp32 on the device (written practically never; it keeps
+ *               the loads alive)
+ *   start/stop  hipEvent_t handles as void* stamped with the kernel's begin
+ *               and end (either may be NULL)
+ */
+int chai_stream_read_probe(const void *buf, size_t bytes, float *sink, void *stream, void *start_event,
+                           void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_as
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention", "chai_decode_step",
            "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
            "chai_dense_decode_attention", "chai_prefill_workspace_bytes", "chai_prefill_attention",
-           "chai_prefill_attention_timed", "chai_dense_prefill_attention", "chai_project_qk", "chai_project_qk_timed"]
+           "chai_prefill_attention_timed", "chai_dense_prefill_attention", "chai_project_qk", "chai_project_qk_timed", "chai_stream_read_probe"]
 
 
 class ChaiError(RuntimeError):
@@ -66,6 +66,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_append_kv_shared_v.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     L.chai_project_qk.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, ci, ci, vp]
     L.chai_project_qk_timed.argtypes = L.chai_project_qk.argtypes + [vp, vp]
+    L.chai_stream_read_probe.argtypes = [vp, sz, vp, vp, vp, vp]
     L.chai_prefill_workspace_bytes.restype = sz
     L.chai_prefill_workspace_bytes.argtypes = [ci, ci, ci, ci]
     L.chai_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
@@ -243,6 +244,13 @@ def chai_project_qk(x, w_q, w_k, rep_heads, q_out, k_compact, pos0: int, stream=
     _check("chai_project_qk",
            _lib.chai_project_qk(_ptr(x), _ptr(w_q), _ptr(w_k), _ptr(rep_heads), B, H, k, Tn, D, d, dtype_code(x),
                                 _ptr(q_out), _ptr(k_compact), pos0, Tc_cap, _stream(stream)))
+
+
+def chai_stream_read_probe(buf, sink, nbytes: Optional[int] = None, stream=None, start_event=None, stop_event=None):
+    """Bare streaming read of a device tensor (measurement aid); sink: one fp32 on the device."""
+    n = buf.numel() * buf.element_size() if nbytes is None else nbytes
+    _check("chai_stream_read_probe",
+           _lib.chai_stream_read_probe(_ptr(buf), n, _ptr(sink), _stream(stream), start_event, stop_event))
 
 
 def chai_decode_workspace_bytes(B: int, H: int, k: int, T: int, d: int, dtype: int) -> int:

@@ -161,6 +161,19 @@ int chai_append_kv(const void *k_new, const void *v_new, const int32_t *rep_head
                                        dtype, static_cast<hipStream_t>(stream)));
 }
 
+int chai_stream_read_probe(const void *buf, size_t bytes, float *sink, void *stream, void *start_event,
+                           void *stop_event)
+{
+    if (!buf || !sink) return CHAI_ERR_NULL;
+    if (bytes == 0 || bytes % 16 != 0) return CHAI_ERR_SHAPE;
+    if (bytes > ((size_t)1 << 40)) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(buf)) return CHAI_ERR_ALIGN;
+    KernelEvents ev;
+    ev.start = static_cast<hipEvent_t>(start_event);
+    ev.stop = static_cast<hipEvent_t>(stop_event);
+    return hip_status(launch_stream_read(buf, bytes, sink, ev, static_cast<hipStream_t>(stream)));
+}
+
 size_t chai_decode_workspace_bytes(int B, int H, int k, int T, int d, int dtype)
 {
     if (B < 0 || H < 1 || k < 1 || k > H || T < 1 || d != kHeadDim || bad_dtype(dtype)) return 0;

@@ -2,6 +2,8 @@
 // kept; all values are kept).  Pure 16-byte copies: bit-exact by construction, bound by HBM bandwidth.
 #include "chai_internal.h"
 
+#include <hip/hip_ext.h>
+
 namespace chai {
 
 namespace {
@@ -75,7 +77,43 @@ __global__ __launch_bounds__(64) void append_shared_kernel(const uint4 *__restri
     else v_compact[((size_t)b * k + j) * vc_stride + (size_t)pos * vec_per_row + lane] = v_new[src];
 }
 
+// Bare streaming read (measurement aid): every workgroup reads `per_wg` consecutive bytes with the same 16-byte
+// non-temporal loads, eight in flight per lane, as the decode kernels use, and adds the words up so that the loads
+// cannot be dropped.  What this kernel reaches is the practical ceiling for the decode kernels on this part.
+__global__ __launch_bounds__(kBlock) void stream_read_kernel(const char *__restrict__ buf, unsigned long long per_wg,
+                                                             unsigned long long bytes, float *__restrict__ sink)
+{
+    typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+    const unsigned long long begin = (unsigned long long)blockIdx.x * per_wg;
+    const unsigned long long nvec = (min(begin + per_wg, bytes) - begin) / 16;
+    const char *base = buf + begin;
+    float acc = 0.f;
+    for (unsigned long long i = threadIdx.x; i < nvec; i += (unsigned long long)kBlock * 8) {
+        u32x4 r[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const unsigned long long j = min(i + (unsigned long long)u * kBlock, nvec - 1);
+            r[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(base + j * 16));
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+            acc += __uint_as_float(r[u].x) + __uint_as_float(r[u].y) + __uint_as_float(r[u].z) + __uint_as_float(r[u].w);
+    }
+    if (acc == 123.456f) sink[0] = acc;          // practically never true: the sum only keeps the loads alive
+}
+
 }  // namespace
+
+int launch_stream_read(const void *buf, size_t bytes, float *sink, const KernelEvents &ev, hipStream_t stream)
+{
+    // about 2048 workgroups (8 per CU), between 64 KiB and 512 KiB each
+    unsigned long long per_wg = ((unsigned long long)bytes / 2048 + 16383) / 16384 * 16384;
+    per_wg = per_wg < 65536 ? 65536 : (per_wg > 524288 ? 524288 : per_wg);
+    const unsigned int n_wg = (unsigned int)((bytes + per_wg - 1) / per_wg);
+    hipExtLaunchKernelGGL(stream_read_kernel, dim3(n_wg), dim3(kBlock), 0, stream, ev.start, ev.stop, 0,
+                          static_cast<const char *>(buf), per_wg, (unsigned long long)bytes, sink);
+    return (int)hipGetLastError();
+}
 
 int launch_append_kv_shared(const void *k_new, const void *v_new, const int32_t *rep, void *k_compact, void *v_compact,
                             int B, int H, int k, int pos, int Tc_cap, int Tv_cap, int dtype, hipStream_t stream)

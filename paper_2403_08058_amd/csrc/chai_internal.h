@@ -88,6 +88,9 @@ int launch_project_qk(const void *x, const void *w_q, const void *w_k, const int
                       int D, void *q_out, void *k_compact, int pos0, int Tc_cap, const KernelEvents &ev,
                       hipStream_t stream);
 
+// bare streaming read of `bytes` (a multiple of 16) bytes; the events cover the kernel
+int launch_stream_read(const void *buf, size_t bytes, float *sink, const KernelEvents &ev, hipStream_t stream);
+
 int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
                           int T_cap, int Tc_cap, int dtype, hipStream_t stream);
 

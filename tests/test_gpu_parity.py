@@ -444,3 +444,15 @@ def test_decode_random_shapes(dtype, B, H, kk, T, T_cap):
     cfg = W.Config("rand", L=1, H=H, d=128, B=B, T=T, T_cap=T_cap, dtype=dtype, ks=(kk,), membership="random",
                    seed=B * 3 + H * 5 + kk * 11 + T)
     G.run_clustered_layer(cfg, W.layer_inputs(cfg, 0))
+
+
+def test_stream_read_probe_runs_and_checks_arguments():
+    buf = torch.ones((1 << 20,), dtype=torch.float32, device="cuda")          # 4 MiB
+    sink = torch.full((1,), 7.0, dtype=torch.float32, device="cuda")
+    C.chai_stream_read_probe(buf, sink)
+    C.chai_stream_read_probe(buf, sink, nbytes=16)
+    torch.cuda.synchronize()
+    assert float(sink[0]) == 7.0
+    with pytest.raises(C.ChaiError) as e:
+        C.chai_stream_read_probe(buf, sink, nbytes=24)                          # not a multiple of 16
+    assert e.value.status == 2
