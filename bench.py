@@ -186,6 +186,22 @@ def read_ceiling(layers, C, torch):
     return rates[len(rates) // 2]
 
 
+def mfma_ceiling(data, C, torch):
+    """Rate of the matrix pipe alone (the library's probe kernel) on operands taken from the workload's own data,
+    in TFLOP/s: what the bf16 MFMAs reach on this device with these values when nothing else is in the way."""
+    hev = HipEvents()
+    sink = torch.zeros((1,), dtype=torch.float32, device="cuda")
+    recs = []
+    for rep in range(4):
+        e0, e1 = hev.create(), hev.create()
+        fl = C.chai_mfma_rate_probe(data, 4000, sink, start_event=e0, stop_event=e1)
+        recs.append((fl, e0, e1))
+    torch.cuda.synchronize()
+    rates = sorted(fl / (hev.elapsed_ms(e0, e1) * 1e-3) / 1e12 for fl, e0, e1 in recs[1:])
+    hev.close()
+    return rates[len(rates) // 2]
+
+
 def read_traffic(cfg_name, kernel="value_kernel"):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 counter summary, if there is one."""
     path = os.path.join(ROOT, "profiles", f"{kernel}_{cfg_name}_hbm_traffic.txt")
@@ -316,6 +332,9 @@ def prefill_main(args, cfg, torch, C, W):
                 "traffic": read_traffic(cfg.name, "prefill_kernel") if T == W.CONFIGS[cfg.name].T else None,
                 "avg_launch_ms": kms, "flops_per_launch": layer_flops[k_dom],
                 "kernel_ms_by_clusters": {str(k): sum(v) / len(v) for k, v in sorted(kern.items())}}
+        ceil_tf = mfma_ceiling(layers[-1].q, C, torch)
+        roof["mfma_ceiling"] = {"TFLOPs": ceil_tf, "frac_of_peak": ceil_tf / 2500.0, "kernel_frac_of_ceiling": ach / ceil_tf,
+                                "how": "matrix pipe alone on the workload's query data (chai_mfma_rate_probe)"}
     else:
         ach = flops / (ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": "whole call (V^T pre-pass, work list, prefill_kernel)", "achieved": ach,
@@ -525,6 +544,10 @@ def project_main(args, cfg, torch, C, W):
         "TFLOPs_whole_step": flops / (ms * 1e-3) / 1e12,
         "host_wall_ms_per_step": wall_ms,
     }
+    ceil_tf = mfma_ceiling(layers[-1].kfull, C, torch)
+    result["roofline"]["mfma_ceiling"] = {"TFLOPs": ceil_tf, "frac_of_peak": ceil_tf / 2500.0,
+                                          "kernel_frac_of_ceiling": ach / ceil_tf,
+                                          "how": "matrix pipe alone on the workload's weight data (chai_mfma_rate_probe)"}
     if dense_ms is not None:
         result["dense_projection"] = {"ms_per_step": dense_ms, "TFLOPs": dense_flops / (dense_ms * 1e-3) / 1e12,
                                       "speedup_pruned_over_dense": dense_ms / ms,

@@ -428,6 +428,21 @@ int chai_project_qk_timed(const void *x, const void *w_q, const void *w_k, const
 int chai_stream_read_probe(const void *buf, size_t bytes, float *sink, void *stream, void *start_event,
                            void *stop_event);
 
+/*
+ * Measurement aid, not a step of the method: the matrix pipe alone.  Every
+ * wave of a chip-filling launch (two waves per SIMD) takes six bf16 operand
+ * fragments from `buf` (device memory, at least 16 bytes, 16-byte aligned;
+ * read modulo its length) and issues `rounds` rounds of eight independent
+ * v_mfma_f32_32x32x16_bf16 with nothing else in the loop.  The rate depends
+ * on the operand values (switching activity moves the clocks), so pass the
+ * data of the workload at hand.  *flops (HOST pointer, may be NULL) receives
+ * the floating-point operations of one launch; sink and the events as for
+ * chai_stream_read_probe.  The benchmark quotes the prefill and projection
+ * kernels against this rate next to the nominal peak.
+ */
+int chai_mfma_rate_probe(const void *buf, size_t bytes, int rounds, float *sink, double *flops, void *stream,
+                         void *start_event, void *stop_event);
+
 #ifdef __cplusplus
 }
 #endif

@@ -27,7 +27,7 @@ EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_as
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention", "chai_decode_step",
            "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
            "chai_dense_decode_attention", "chai_prefill_workspace_bytes", "chai_prefill_attention",
-           "chai_prefill_attention_timed", "chai_dense_prefill_attention", "chai_project_qk", "chai_project_qk_timed", "chai_stream_read_probe"]
+           "chai_prefill_attention_timed", "chai_dense_prefill_attention", "chai_project_qk", "chai_project_qk_timed", "chai_stream_read_probe", "chai_mfma_rate_probe"]
 
 
 class ChaiError(RuntimeError):
@@ -67,6 +67,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_project_qk.argtypes = [vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, vp, vp, ci, ci, vp]
     L.chai_project_qk_timed.argtypes = L.chai_project_qk.argtypes + [vp, vp]
     L.chai_stream_read_probe.argtypes = [vp, sz, vp, vp, vp, vp]
+    L.chai_mfma_rate_probe.argtypes = [vp, sz, ci, vp, ctypes.POINTER(ctypes.c_double), vp, vp, vp]
     L.chai_prefill_workspace_bytes.restype = sz
     L.chai_prefill_workspace_bytes.argtypes = [ci, ci, ci, ci]
     L.chai_prefill_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
@@ -244,6 +245,15 @@ def chai_project_qk(x, w_q, w_k, rep_heads, q_out, k_compact, pos0: int, stream=
     _check("chai_project_qk",
            _lib.chai_project_qk(_ptr(x), _ptr(w_q), _ptr(w_k), _ptr(rep_heads), B, H, k, Tn, D, d, dtype_code(x),
                                 _ptr(q_out), _ptr(k_compact), pos0, Tc_cap, _stream(stream)))
+
+
+def chai_mfma_rate_probe(buf, rounds: int, sink, stream=None, start_event=None, stop_event=None) -> float:
+    """The matrix pipe alone on operands taken from `buf` (measurement aid); returns the flops of the launch."""
+    flops = ctypes.c_double(0.0)
+    _check("chai_mfma_rate_probe",
+           _lib.chai_mfma_rate_probe(_ptr(buf), buf.numel() * buf.element_size(), rounds, _ptr(sink), ctypes.byref(flops),
+                                     _stream(stream), start_event, stop_event))
+    return float(flops.value)
 
 
 def chai_stream_read_probe(buf, sink, nbytes: Optional[int] = None, stream=None, start_event=None, stop_event=None):

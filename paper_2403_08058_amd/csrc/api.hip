@@ -161,6 +161,19 @@ int chai_append_kv(const void *k_new, const void *v_new, const int32_t *rep_head
                                        dtype, static_cast<hipStream_t>(stream)));
 }
 
+int chai_mfma_rate_probe(const void *buf, size_t bytes, int rounds, float *sink, double *flops, void *stream,
+                         void *start_event, void *stop_event)
+{
+    if (!buf || !sink) return CHAI_ERR_NULL;
+    if (bytes < 16 || rounds < 1) return CHAI_ERR_SHAPE;
+    if (!aligned16(buf)) return CHAI_ERR_ALIGN;
+    if (flops) *flops = mfma_probe_flops(rounds);
+    KernelEvents ev;
+    ev.start = static_cast<hipEvent_t>(start_event);
+    ev.stop = static_cast<hipEvent_t>(stop_event);
+    return hip_status(launch_mfma_probe(buf, bytes, rounds, sink, ev, static_cast<hipStream_t>(stream)));
+}
+
 int chai_stream_read_probe(const void *buf, size_t bytes, float *sink, void *stream, void *start_event,
                            void *stop_event)
 {

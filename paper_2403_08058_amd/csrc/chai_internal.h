@@ -88,6 +88,10 @@ int launch_project_qk(const void *x, const void *w_q, const void *w_k, const int
                       int D, void *q_out, void *k_compact, int pos0, int Tc_cap, const KernelEvents &ev,
                       hipStream_t stream);
 
+// the matrix pipe alone: `rounds` rounds of 8 MFMAs per wave on operands taken from buf; flops of one launch
+int launch_mfma_probe(const void *buf, size_t bytes, int rounds, float *sink, const KernelEvents &ev, hipStream_t stream);
+double mfma_probe_flops(int rounds);
+
 // bare streaming read of `bytes` (a multiple of 16) bytes; the events cover the kernel
 int launch_stream_read(const void *buf, size_t bytes, float *sink, const KernelEvents &ev, hipStream_t stream);
 

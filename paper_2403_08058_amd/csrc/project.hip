@@ -159,7 +159,52 @@ __global__ __launch_bounds__(kJBlock) void project_kernel(const char *__restrict
     }
 }
 
+// Measurement aid: the matrix pipe alone.  Every wave (two per SIMD on every CU) loads six operand fragments from
+// `buf` once and then issues rounds of eight independent v_mfma_f32_32x32x16_bf16 with nothing else in the loop.
+// The rate depends on the operand VALUES (switching activity moves the clocks), hence operands from the caller's
+// data rather than constants.
+constexpr int kProbeBlocks = 512, kProbeMfmaPerRound = 8;
+__global__ __launch_bounds__(kJBlock) void mfma_probe_kernel(const u32x4 *__restrict__ buf, unsigned long long n_pieces,
+                                                             int rounds, float *__restrict__ sink)
+{
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    Frag a[2], b[4];
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        const unsigned long long at = (((unsigned long long)blockIdx.x * 8 + w) * 6 + i) * 64 + lane;
+        (i < 2 ? a[i] : b[i - 2]).raw = buf[at % n_pieces];
+    }
+    f32x16 acc[kProbeMfmaPerRound];
+#pragma unroll
+    for (int i = 0; i < kProbeMfmaPerRound; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+    for (int it = 0; it < rounds; ++it) {
+#pragma unroll
+        for (int i = 0; i < kProbeMfmaPerRound; ++i)
+            acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i & 1].bf, b[i >> 1].bf, acc[i], 0, 0, 0);
+    }
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < kProbeMfmaPerRound; ++i)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) t += acc[i][e];
+    if (t == 123.456f) sink[0] = t;              // practically never true: keeps the MFMAs alive
+}
+
 }  // namespace
+
+double mfma_probe_flops(int rounds)
+{
+    return (double)kProbeBlocks * (kJBlock / 64) * (double)rounds * kProbeMfmaPerRound * (2.0 * 32 * 32 * 16);
+}
+
+int launch_mfma_probe(const void *buf, size_t bytes, int rounds, float *sink, const KernelEvents &ev, hipStream_t stream)
+{
+    hipExtLaunchKernelGGL(mfma_probe_kernel, dim3(kProbeBlocks), dim3(kJBlock), 0, stream, ev.start, ev.stop, 0,
+                          static_cast<const u32x4 *>(buf), (unsigned long long)(bytes / 16), rounds, sink);
+    return (int)hipGetLastError();
+}
 
 int launch_project_qk(const void *x, const void *w_q, const void *w_k, const int32_t *rep, int B, int H, int k, int Tn,
                       int D, void *q_out, void *k_compact, int pos0, int Tc_cap, const KernelEvents &ev,

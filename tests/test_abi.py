@@ -24,7 +24,7 @@ def declared_functions():
 
 def test_header_symbols_exported(chai):
     names = declared_functions()
-    assert len(names) == 26 and "chai_assign_clusters" in names and "chai_compact_kcache" in names \
+    assert len(names) == 27 and "chai_assign_clusters" in names and "chai_compact_kcache" in names \
         and "chai_decode_attention" in names
     L = ctypes.CDLL(chai.LIB_PATH)
     for n in names:

@@ -131,3 +131,14 @@ def test_projection_argument_errors():
     assert e.value.status == 5
     torch.cuda.synchronize()
     assert bool((q == 7.0).all()) and bool((kc == 7.0).all())
+
+
+def test_mfma_rate_probe_runs_and_checks_arguments():
+    data = torch.randn((1 << 16,), device="cuda").to(torch.bfloat16)
+    sink = torch.full((1,), 7.0, dtype=torch.float32, device="cuda")
+    flops = C.chai_mfma_rate_probe(data, 10, sink)
+    torch.cuda.synchronize()
+    assert flops == 512 * 8 * 10 * 8 * 2.0 * 32 * 32 * 16 and float(sink[0]) == 7.0
+    with pytest.raises(C.ChaiError) as e:
+        C.chai_mfma_rate_probe(data, 0, sink)
+    assert e.value.status == 2
