@@ -315,6 +315,17 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     // V^T buffer vbuf.  HAS_NEXT: the scores of the wave's next block (K buffer nbuf, half nhalf) are issued in the
     // same stretch of code as the exponentials, one MFMA per handful of vector instructions, so that the matrix
     // pipe is busy while this wave exponentiates; they are returned.
+    // Wave priority: raised while a wave is in the stretch that mixes vector work with score MFMAs, so that the
+    // SIMD's arbiter favours it over the other wave's back-to-back value MFMAs, which lose nothing by waiting a
+    // few cycles (measured: 1.5-4 % faster).
+    auto wave_priority = [](bool high) {
+#if defined(__HIP_DEVICE_COMPILE__)
+        if (high) __builtin_amdgcn_s_setprio(2);
+        else __builtin_amdgcn_s_setprio(0);
+#else
+        (void)high;
+#endif
+    };
     auto block = [&](f32x16 st, int kbase, int vbuf, int half, auto has_next, int nbuf, int nhalf) {
         constexpr bool HAS_NEXT = decltype(has_next)::value;
         // causal mask: only blocks that reach past the wave's first query need it (a real branch, uniform per
@@ -352,6 +363,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         }
         m_run = m_new;
 
+        wave_priority(true);
         f32x16 s_next = st;
         float rs = 0.f;
         Frag16 pf[2];
@@ -390,6 +402,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         float rs_lo, rs_hi;
         both_halves(rs, rs_lo, rs_hi);
         l_run += rs_lo + rs_hi;
+        wave_priority(false);
         // O^T[d][query] += V^T P^T for every member head: fragment j = (blk, s) of a member, requested
         // kVAhead MFMAs before its use so that the LDS latency hides behind the matrix pipe
 #pragma unroll
