@@ -19,13 +19,9 @@
  * the shared-value ablation against dense attention of the representative,
  * the nearest-to-mean representative against hand-worked cases and numpy,
  * the representatives' projections against a library contraction.
- * Unpinned: no function of this file.  One clause inside chai_oracle_kmeans
- * is a safeguard that no example separates from its relaxation: an empty
- * centre takes a head only from a cluster that holds at least two ("at least
- * one" gave the same partitions on 500 000 random small problems), so that
- * clause is parity unpinned as a rule on its own.  (How well clustered
- * attention approximates dense attention on trained models is not computed
- * here at all; it needs weights and datasets.)
+ * Unpinned: no function of this file.  (How well clustered attention
+ * approximates dense attention on trained models is not computed here at
+ * all; it needs weights and datasets.)
  *
  * All pointers are HOST pointers.  dtype: 0 = fp32, 1 = bf16 (raw uint16
  * bit patterns, converted exactly by placing them in the top half of an
@@ -513,9 +509,10 @@ int chai_oracle_pick_cluster_count(const double *err, const int32_t *ks, int n, 
  *     head with the largest distance to its own centre among heads whose
  *     cluster holds at least two heads (ties: lowest head; a largest
  *     distance of zero leaves j empty) and move it to j.  (The "at least two
- *     heads" condition guarantees a repair never empties another cluster; no
- *     input was found on which dropping it changes the result, so that one
- *     condition has no example pinning it.)
+ *     heads" condition keeps a repair from emptying another cluster behind
+ *     the scan: a lone head can be the farthest on the board, because its
+ *     distance is measured to the centre of the previous pass; hand-worked
+ *     examples of exactly that pin the condition.)
  *  4. if this is not the first pass and no head changed cluster: stop.
  *  5. update: each non-empty centre becomes the mean of its heads (summed
  *     in head order, then divided by the count); an empty centre stays.

@@ -5,10 +5,9 @@ comparison ...), builds the broken copy in a temporary directory and runs the pi
 A pin set that lets a mutant through is too weak to vouch for the oracle.  The mistakes are planted in the
 oracle, on the CPU; the HIP library is not involved.
 
-Not in the list: relaxing the repair rule's "donor cluster holds at least two heads" to "at least one".  On
-500 000 random small problems (1-D and 2-D integer points, 4-9 heads, 3-4 centres) the relaxed rule returned the
-same partitions, so no example separates the two; the restriction is a safeguard (a repair can never empty
-another cluster) and is listed as such in the oracle's header.
+The repair rule's donor condition ("the donor cluster holds at least two heads") has its own mutant: hand-worked
+cases in tests/golden/kmeans_worked.json have a lone head that is the farthest on the board while another centre is
+empty, so taking it changes the partition (or the number of passes).
 """
 import os
 import subprocess
@@ -55,6 +54,8 @@ MUTANTS = [
     ("kmeans_mean_not_divided", "centre[j * F + f] = acc / (double)count[j];", "centre[j * F + f] = acc;", 0,
      ["pin_kmeans_worked_examples"]),
     ("kmeans_repair_takes_zero_distance", "dmin[h] > far) { far = dmin[h]; pick = h; }", "dmin[h] >= far) { far = dmin[h]; pick = h; }", 0,
+     ["pin_kmeans_worked_examples"]),
+    ("kmeans_repair_takes_a_lone_head", "if (count[assign[h]] >= 2 && dmin[h] > far)", "if (count[assign[h]] >= 1 && dmin[h] > far)", 0,
      ["pin_kmeans_worked_examples"]),
     ("kmeans_never_stops_early", "if (!changed || it >= max_iter) break;", "if (it >= max_iter) break;", 0,
      ["pin_kmeans_worked_examples"]),
