@@ -2,6 +2,8 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+
+#include <atomic>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -27,15 +29,17 @@ DecodePlan make_decode_plan(int B, int H, int k, int T);
 
 // Kernels that use more than 64 KB of dynamic LDS must be told so once on every device they run on.  `done` is the
 // caller's per-kernel table (zero-initialised, one flag per device ordinal); a repeated call costs one hipGetDevice.
+// The flags are atomics: any thread may call; setting the attribute twice in a race is harmless.
 constexpr int kMaxDevices = 64;
-inline hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, bool (&done)[kMaxDevices])
+typedef std::atomic<bool> DeviceFlags[kMaxDevices];
+inline hipError_t allow_dynamic_lds(const void *kernel, size_t bytes, DeviceFlags &done)
 {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return e;
-    if (dev >= 0 && dev < kMaxDevices && done[dev]) return hipSuccess;
+    if (dev >= 0 && dev < kMaxDevices && done[dev].load(std::memory_order_acquire)) return hipSuccess;
     e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
-    if (e == hipSuccess && dev >= 0 && dev < kMaxDevices) done[dev] = true;
+    if (e == hipSuccess && dev >= 0 && dev < kMaxDevices) done[dev].store(true, std::memory_order_release);
     return e;
 }
 

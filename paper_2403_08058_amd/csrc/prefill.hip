@@ -521,7 +521,7 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     vt_kernel<<<dim3(Tp / kKTile, H, B), 256, 0, stream>>>(static_cast<const char *>(v), H, T_cap, n_keys, Tp, vt);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return (int)e;
-    static bool lds_ident[kMaxDevices], lds_clustered[kMaxDevices];
+    static DeviceFlags lds_ident, lds_clustered;
     e = allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<true>), prefill_lds_bytes(true), lds_ident);
     if (e != hipSuccess) return (int)e;
     e = allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<false>), prefill_lds_bytes(false), lds_clustered);

@@ -210,7 +210,7 @@ int launch_project_qk(const void *x, const void *w_q, const void *w_k, const int
                       int D, void *q_out, void *k_compact, int pos0, int Tc_cap, const KernelEvents &ev,
                       hipStream_t stream)
 {
-    static bool lds_allowed[kMaxDevices];
+    static DeviceFlags lds_allowed;
     const hipError_t attr = allow_dynamic_lds(reinterpret_cast<const void *>(&project_kernel), kJLdsBytes, lds_allowed);
     if (attr != hipSuccess) return (int)attr;
     const int n_mt = (Tn + kJTok - 1) / kJTok;
