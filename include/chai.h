@@ -11,7 +11,10 @@
  * Conventions for every entry point
  *  - All tensor pointers are DEVICE pointers owned by the caller.  The
  *    library allocates nothing, frees nothing and keeps no pointer after the
- *    call returns.  There is no global state.
+ *    call returns.  Its only process-wide state is bookkeeping that does not
+ *    affect results: per-device "attribute already set" flags of the kernels
+ *    with large LDS, and the fixed scratch array of
+ *    chai_decode_attention_static with its per-device address table.
  *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *    Calls only enqueue work on it: no synchronisation, no host read-back.
  *    Cluster maps produced by one call are consumed by the next on the device.
@@ -49,8 +52,12 @@ enum {
     CHAI_ERR_WORKSPACE = 4,   /* workspace NULL, misaligned or smaller than required */
     CHAI_ERR_UNSUPPORTED = 5, /* valid request this build does not implement (d != 128, ...) */
     CHAI_ERR_HIP = 6,         /* the HIP runtime reported an error at launch         */
-    CHAI_ERR_ALIGN = 7        /* a tensor pointer is not 16-byte aligned             */
+    CHAI_ERR_ALIGN = 7,       /* a tensor pointer is not 16-byte aligned             */
+    CHAI_ERR_STATIC_LIMIT = 8 /* chai_decode_attention_static: sizes need more than CHAI_STATIC_SCRATCH_BYTES */
 };
+
+/* Size of the scratch array built into the library for chai_decode_attention_static. */
+#define CHAI_STATIC_SCRATCH_BYTES (32u << 20)
 
 enum { CHAI_F32 = 0, CHAI_BF16 = 1 };
 
@@ -227,6 +234,31 @@ int chai_decode_attention(const void *q, const void *k_compact, const void *v_ca
                           int k, int T, int Tc_cap, int T_cap, int d, int dtype, float scale,
                           float *out, float *probs_out, void *workspace, size_t workspace_bytes,
                           void *stream);
+
+/*
+ * chai_decode_attention for callers that cannot allocate device memory or
+ * carry a workspace around: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and
+ * same results as chai_decode_attention, minus the workspace: scores, chunk
+ * statistics and partial rows live in a fixed array of
+ * CHAI_STATIC_SCRATCH_BYTES (32 MiB) that is part of the library's code
+ * object; every GPU the library runs on holds its own copy until the process
+ * ends.  The call allocates and frees nothing (its first call on a device
+ * looks up the array's address once).
+ *   - Sizes whose chai_decode_workspace_bytes(B, H, k, T, d, dtype) exceeds
+ *     CHAI_STATIC_SCRATCH_BYTES are refused with CHAI_ERR_STATIC_LIMIT
+ *     before anything is launched (use chai_decode_attention then).
+ *   - Nothing in the array has to start at zero: every location a call reads
+ *     it has written first, so stale contents of an earlier, larger call are
+ *     harmless.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in
+ *     time on one GPU (two streams, two threads) race.  Serialise them, or
+ *     give the overlapping ones chai_decode_attention with workspaces.
+ */
+int chai_decode_attention_static(const void *q, const void *k_compact, const void *v_cache,
+                                 const int32_t *head_to_cluster, const int32_t *rep_heads, int B,
+                                 int H, int k, int T, int Tc_cap, int T_cap, int d, int dtype,
+                                 float scale, float *out, float *probs_out, void *stream);
 
 /*
  * The two phases of chai_decode_attention as separate calls (same arguments,

@@ -19,12 +19,14 @@ LIB_PATH = os.path.join(_HERE, "libchai.so")
 CHAI_OK = 0
 CHAI_F32, CHAI_BF16 = 0, 1
 STATUS_NAMES = {0: "CHAI_OK", 1: "CHAI_ERR_NULL", 2: "CHAI_ERR_SHAPE", 3: "CHAI_ERR_DTYPE", 4: "CHAI_ERR_WORKSPACE",
-                5: "CHAI_ERR_UNSUPPORTED", 6: "CHAI_ERR_HIP", 7: "CHAI_ERR_ALIGN"}
+                5: "CHAI_ERR_UNSUPPORTED", 6: "CHAI_ERR_HIP", 7: "CHAI_ERR_ALIGN", 8: "CHAI_ERR_STATIC_LIMIT"}
+CHAI_STATIC_SCRATCH_BYTES = 32 << 20
 
 EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_assign_clusters",
            "chai_cluster_error", "chai_pick_cluster_count", "chai_closest_representatives",
            "chai_decode_attention_shared_v", "chai_append_kv_shared_v",
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention", "chai_decode_step",
+           "chai_decode_attention_static",
            "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
            "chai_dense_decode_attention", "chai_prefill_workspace_bytes", "chai_prefill_attention",
            "chai_prefill_attention_timed", "chai_dense_prefill_attention", "chai_project_qk", "chai_project_qk_timed", "chai_stream_read_probe", "chai_mfma_rate_probe"]
@@ -55,6 +57,7 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_decode_workspace_bytes.restype = sz
     L.chai_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
     L.chai_decode_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, vp, sz, vp]
+    L.chai_decode_attention_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, vp]
     L.chai_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     L.chai_dense_decode_attention.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     L.chai_decode_scores.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
@@ -278,6 +281,19 @@ def chai_decode_attention(q, k_compact, v_cache, head_to_cluster, rep_heads, T: 
                                       B, H, k, T, Tc_cap, T_cap, d, dtype_code(q), scale, _ptr(out), _ptr(probs_out),
                                       _ptr(workspace), workspace.numel() * workspace.element_size(),
                                       _stream(stream)))
+    return out
+
+
+def chai_decode_attention_static(q, k_compact, v_cache, head_to_cluster, rep_heads, T: int, scale: float, out,
+                                 probs_out=None, stream=None):
+    """chai_decode_attention without a workspace: scratch is a fixed array inside the library (no allocation)."""
+    B, H, d = q.shape
+    k, Tc_cap = k_compact.shape[1], k_compact.shape[2]
+    T_cap = v_cache.shape[2]
+    _check("chai_decode_attention_static",
+           _lib.chai_decode_attention_static(_ptr(q), _ptr(k_compact), _ptr(v_cache), _ptr(head_to_cluster),
+                                             _ptr(rep_heads), B, H, k, T, Tc_cap, T_cap, d, dtype_code(q), scale,
+                                             _ptr(out), _ptr(probs_out), _stream(stream)))
     return out
 
 

@@ -2,9 +2,39 @@
 // allocates, synchronises or reads device memory.
 #include "chai_internal.h"
 
+#include <mutex>
+
 using namespace chai;
 
+// Scratch of chai_decode_attention_static: a fixed array inside the library's code object, so the entry point
+// needs no workspace from the caller and no allocation.  Every GPU the library runs on holds its own copy (at
+// its own address) until the process ends.  In host code the NAME below is only a handle for
+// hipGetSymbolAddress; kernels get the looked-up device address.
+static __device__ __align__(256) unsigned char scratch[CHAI_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+std::mutex g_scratch_lock;
+void *g_scratch_ptr[kMaxDevices];      // device address of `scratch` on each device, looked up once
+
+// Address of the current device's copy of `scratch` (first call on a device looks it up; no allocation).
+hipError_t static_scratch(void **out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return hipSuccess;
+}
 
 constexpr int kVersion = 100;
 constexpr int kMaxGridYZ = 65535;
@@ -63,6 +93,7 @@ const char *chai_status_string(int status)
     case CHAI_ERR_UNSUPPORTED: return "sizes not supported by this build";
     case CHAI_ERR_HIP: return "HIP runtime error at kernel launch";
     case CHAI_ERR_ALIGN: return "tensor pointer not 16-byte aligned";
+    case CHAI_ERR_STATIC_LIMIT: return "sizes need more scratch than the library's static buffer holds";
     default: return "unknown status";
     }
 }
@@ -260,6 +291,30 @@ int chai_decode_attention(const void *q, const void *k_compact, const void *v_ca
     if (st != CHAI_OK) return st;
     return hip_status(launch_values(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, dtype, out, probs_out,
                                     workspace, plan, false, KernelEvents(), s));
+}
+
+int chai_decode_attention_static(const void *q, const void *k_compact, const void *v_cache,
+                                 const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H, int k, int T,
+                                 int Tc_cap, int T_cap, int d, int dtype, float scale, float *out, float *probs_out,
+                                 void *stream)
+{
+    if (!head_to_cluster || !rep_heads) return CHAI_ERR_NULL;
+    // sizes first, with a stand-in workspace of the full static size: a plan that needs more is refused here
+    DecodePlan plan;
+    int st = check_scores(q, k_compact, B, H, k, T, Tc_cap, d, dtype, nullptr, 0, &plan);
+    if (st == CHAI_OK || st == CHAI_ERR_WORKSPACE)
+        st = check_values(v_cache, out, B, H, k, T, T_cap, d, dtype, nullptr, 0, &plan);
+    if (st != CHAI_OK && st != CHAI_ERR_WORKSPACE) return st;
+    if (B == 0) return CHAI_OK;
+    if (plan.bytes > (size_t)CHAI_STATIC_SCRATCH_BYTES) return CHAI_ERR_STATIC_LIMIT;
+    void *ws = nullptr;
+    if (static_scratch(&ws) != hipSuccess) return CHAI_ERR_HIP;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    st = hip_status(launch_scores(q, k_compact, rep_heads, B, H, k, T, Tc_cap, dtype, scale, ws, plan, false,
+                                  KernelEvents(), s));
+    if (st != CHAI_OK) return st;
+    return hip_status(launch_values(v_cache, head_to_cluster, rep_heads, B, H, k, T, T_cap, dtype, out, probs_out, ws,
+                                    plan, false, KernelEvents(), s));
 }
 
 int chai_decode_step(const void *q, const void *k_new, const void *v_new, void *k_compact, void *v_cache,
