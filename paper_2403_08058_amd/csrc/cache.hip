@@ -110,20 +110,18 @@ int launch_stream_read(const void *buf, size_t bytes, float *sink, const KernelE
     unsigned long long per_wg = ((unsigned long long)bytes / 2048 + 16383) / 16384 * 16384;
     per_wg = per_wg < 65536 ? 65536 : (per_wg > 524288 ? 524288 : per_wg);
     const unsigned int n_wg = (unsigned int)((bytes + per_wg - 1) / per_wg);
-    hipExtLaunchKernelGGL(stream_read_kernel, dim3(n_wg), dim3(kBlock), 0, stream, ev.start, ev.stop, 0,
-                          static_cast<const char *>(buf), per_wg, (unsigned long long)bytes, sink);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(stream_read_kernel, dim3(n_wg), dim3(kBlock), 0, stream, ev, static_cast<const char *>(buf),
+                              per_wg, (unsigned long long)bytes, sink);
 }
 
 int launch_append_kv_shared(const void *k_new, const void *v_new, const int32_t *rep, void *k_compact, void *v_compact,
                             int B, int H, int k, int pos, int Tc_cap, int Tv_cap, int dtype, hipStream_t stream)
 {
     const int vec_per_row = kHeadDim * (dtype == CHAI_BF16 ? 2 : 4) / 16;
-    append_shared_kernel<<<dim3(2 * k, B), 64, 0, stream>>>(
-        static_cast<const uint4 *>(k_new), static_cast<const uint4 *>(v_new), rep, static_cast<uint4 *>(k_compact),
-        static_cast<uint4 *>(v_compact), H, k, pos, (long long)Tc_cap * vec_per_row, (long long)Tv_cap * vec_per_row,
-        vec_per_row);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(append_shared_kernel, dim3(2 * k, B), dim3(64), 0, stream, KernelEvents(),
+                              static_cast<const uint4 *>(k_new), static_cast<const uint4 *>(v_new), rep,
+                              static_cast<uint4 *>(k_compact), static_cast<uint4 *>(v_compact), H, k, pos,
+                              (long long)Tc_cap * vec_per_row, (long long)Tv_cap * vec_per_row, vec_per_row);
 }
 
 int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compact, int B, int H, int k, int T,
@@ -133,23 +131,19 @@ int launch_compact_kcache(const void *k_full, const int32_t *rep, void *k_compac
     const long long vec_per_stream = (long long)T * vec_per_row;
     const long long per_block = (long long)kBlock * kCopyUnroll;
     const unsigned int gx = (unsigned int)((vec_per_stream + per_block - 1) / per_block);
-    compact_kernel<<<dim3(gx, k, B), kBlock, 0, stream>>>(static_cast<const uint4 *>(k_full), rep,
-                                                          static_cast<uint4 *>(k_compact), H, k, vec_per_stream,
-                                                          (long long)T_cap * vec_per_row,
-                                                          (long long)Tc_cap * vec_per_row);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(compact_kernel, dim3(gx, k, B), dim3(kBlock), 0, stream, KernelEvents(),
+                              static_cast<const uint4 *>(k_full), rep, static_cast<uint4 *>(k_compact), H, k,
+                              vec_per_stream, (long long)T_cap * vec_per_row, (long long)Tc_cap * vec_per_row);
 }
 
 int launch_append_kv(const void *k_new, const void *v_new, const int32_t *rep, void *k_compact, void *v_cache, int B,
                      int H, int k, int pos, int Tc_cap, int T_cap, int dtype, hipStream_t stream)
 {
     const int vec_per_row = kHeadDim * (dtype == CHAI_BF16 ? 2 : 4) / 16;
-    append_kernel<<<dim3(k + H, B), 64, 0, stream>>>(static_cast<const uint4 *>(k_new),
-                                                     static_cast<const uint4 *>(v_new), rep,
-                                                     static_cast<uint4 *>(k_compact), static_cast<uint4 *>(v_cache),
-                                                     H, k, pos, (long long)Tc_cap * vec_per_row,
-                                                     (long long)T_cap * vec_per_row, vec_per_row);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(append_kernel, dim3(k + H, B), dim3(64), 0, stream, KernelEvents(),
+                              static_cast<const uint4 *>(k_new), static_cast<const uint4 *>(v_new), rep,
+                              static_cast<uint4 *>(k_compact), static_cast<uint4 *>(v_cache), H, k, pos,
+                              (long long)Tc_cap * vec_per_row, (long long)T_cap * vec_per_row, vec_per_row);
 }
 
 }  // namespace chai

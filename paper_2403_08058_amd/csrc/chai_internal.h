@@ -17,8 +17,9 @@ constexpr int kBlock = 256;         // threads per workgroup of the streaming ke
 // How one decode call is cut into workgroups.  Derived from the sizes alone, so the workspace query and the
 // call itself always agree.
 struct DecodePlan {
-    int cs;          // tokens per workgroup of the score kernel (one softmax-statistics record each)
+    int cs;          // tokens per workgroup of the score kernel
     int n_cs;        // score chunks per (b, cluster) = ceil(T / cs)
+    int n_rec;       // softmax-statistics records per (b, cluster): one per wave of every score workgroup
     int cp;          // tokens per workgroup of the value kernel
     int n_cp;        // value chunks per (b, head) = ceil(T / cp)
     int ds;          // workgroups per (b, head, chunk) of the value kernel: 1, or 2 with half of the columns each
@@ -48,6 +49,22 @@ struct KernelEvents {
     hipEvent_t start = nullptr;
     hipEvent_t stop = nullptr;
 };
+
+// Kernel launch that reports the status of THIS launch: the return value of the runtime's launch call, not the
+// thread's sticky "last error" (which may hold, and would clear, an unrelated earlier error of the caller).
+// Arguments are converted to the kernel's own parameter types; the events may be NULL.
+template <typename T>
+struct same_type {
+    typedef T type;
+};
+template <typename... KArgs>
+inline hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, size_t lds_bytes, hipStream_t stream,
+                                const KernelEvents &ev, typename same_type<KArgs>::type... args)
+{
+    void *argv[] = {const_cast<void *>(static_cast<const void *>(&args))...};
+    return hipExtLaunchKernel(reinterpret_cast<const void *>(kernel), grid, block, argv, lds_bytes, stream, ev.start,
+                              ev.stop, 0);
+}
 
 // Enqueue the two kernels of one decode call.  identity = true: every head is its own cluster and the maps
 // are not read (dense attention).  k_new / v_new [B,H,d] (clustered calls only): position T-1 is the token being

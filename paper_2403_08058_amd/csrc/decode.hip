@@ -10,17 +10,13 @@
 
 #include <hip/hip_ext.h>
 
-#ifdef CHAI_TUNING
-#include <cstdlib>
-#endif
-
 namespace chai {
 
 namespace {
 
 constexpr int kUnroll = 8;        // 16-byte loads per lane in one batch
-constexpr int kMaxCs = 256;       // largest score chunk (= workgroup size: one thread per score)
-constexpr int kWaves = kBlock / 64;   // waves per workgroup of the score kernel
+constexpr int kScoreWaves = 4;    // waves per workgroup of the score kernel ...
+constexpr int kScoreBatches = 2;  // ... each with this many batches in flight
 
 template <bool BF16>
 struct Tile {
@@ -101,130 +97,6 @@ __device__ __forceinline__ float wave_sum(float x)
     return x;
 }
 
-// Workgroup-wide reductions over the waves; `red` is kWaves floats of LDS, reusable right after return.
-__device__ __forceinline__ float block_max(float x, float *red)
-{
-    x = wave_max(x);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
-    __syncthreads();
-    x = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-    __syncthreads();
-    return x;
-}
-
-__device__ __forceinline__ float block_sum(float x, float *red)
-{
-    x = wave_sum(x);
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = x;
-    __syncthreads();
-    x = (red[0] + red[1]) + (red[2] + red[3]);
-    __syncthreads();
-    return x;
-}
-
-// Row (relative to the start of the chunk) that lane group `rg` of wave `w` reads with load `u` of its
-// `it`-th batch: batches of BATCH consecutive rows are dealt to the waves round-robin.
-template <bool BF16>
-__device__ __forceinline__ int batch_row(int it, int w, int u, int rg)
-{
-    return (it * kWaves + w) * Tile<BF16>::BATCH + u * Tile<BF16>::RPW + rg;
-}
-
-// ---------------------------------------------------------------------------------------------------------
-// Score kernel: s[b][j][t] = scale * q[b][rep(b,j)] . Kc[b][j][t], plus (max, sum of exp) per chunk of cs
-// tokens.  grid = (n_cs, k, B).
-// APPEND: the last position, T-1, is the token being decoded: its key is not in the cache yet.  The workgroup of
-// the last chunk takes it from k_new [B,H,d] (row of the representative), scores it, and writes it to the cache,
-// so that growing the cache costs no launch of its own.
-// ---------------------------------------------------------------------------------------------------------
-template <bool BF16, bool IDENT, bool APPEND>
-__global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ q, const char *__restrict__ kc,
-                                                       const int32_t *__restrict__ rep, int H, int k, int T,
-                                                       int Tc_cap, float scale, int cs, int n_cs,
-                                                       float *__restrict__ scores, float2 *__restrict__ stats,
-                                                       const char *__restrict__ k_new)
-{
-    using TL = Tile<BF16>;
-    __shared__ float s_lds[kMaxCs];
-    __shared__ float red[kWaves];
-
-    const int tid = threadIdx.x;
-    const int chunk = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
-
-
-    const int lane = tid & 63, w = tid >> 6;
-    const int cg = lane % TL::LPR, rg = lane / TL::LPR;
-    const int t0 = chunk * cs;
-    const int n = min(T, t0 + cs) - t0;      // >= 1 by construction of n_cs
-    const bool has_new = APPEND && chunk == n_cs - 1;        // this chunk ends with the token being decoded
-    const int n_old = has_new ? n - 1 : n;                   // rows that are in the cache already
-
-    const char *kbase = kc + (((size_t)b * k + j) * Tc_cap + t0) * TL::ROW_BYTES + cg * 16;
-    const int n_it = (n_old + TL::BATCH * kWaves - 1) / (TL::BATCH * kWaves);
-
-    // Every load of the chunk is issued before anything else (cs <= 256: at most 2 batches per wave in bf16, 4
-    // in fp32), including the lookup of the representative: the key stream of a cluster slot does not depend
-    // on who represents it, and an unused slot's keys are still readable memory.
-    constexpr int kMaxIt = kMaxCs / (TL::BATCH * kWaves);
-    u32x4 raw[kMaxIt][kUnroll];
-#pragma unroll
-    for (int it = 0; it < kMaxIt; ++it) {
-        if (it < n_it) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u)
-                raw[it][u] = stream16(kbase + (size_t)min(batch_row<BF16>(it, w, u, rg), n_old - 1) * TL::ROW_BYTES);
-        }
-    }
-
-    int r = IDENT ? j : rep[(size_t)b * k + j];
-    if (r < 0) return;                       // unused cluster slot (same decision for the whole workgroup)
-    r = min(r, H - 1);
-
-    float qf[TL::EPL];
-    {
-        const u32x4 qraw = *reinterpret_cast<const u32x4 *>(q + ((size_t)b * H + r) * TL::ROW_BYTES + cg * 16);
-        unpack(qraw, qf);
-    }
-
-#pragma unroll
-    for (int it = 0; it < kMaxIt; ++it) {
-        if (it < n_it) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const int tl = batch_row<BF16>(it, w, u, rg);
-                float f[TL::EPL];
-                unpack(raw[it][u], f);
-                float dot = 0.f;
-#pragma unroll
-                for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
-                dot = row_sum<BF16>(dot);
-                if (cg == 0 && tl < n_old) s_lds[tl] = scale * dot;
-            }
-        }
-    }
-    if (APPEND) {
-        if (has_new && w == 0 && rg == 0) {      // one lane group: the new key row of the representative
-            const u32x4 nraw = *reinterpret_cast<const u32x4 *>(k_new + ((size_t)b * H + r) * TL::ROW_BYTES + cg * 16);
-            float f[TL::EPL];
-            unpack(nraw, f);
-            float dot = 0.f;
-#pragma unroll
-            for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
-            dot = row_sum<BF16>(dot);
-            if (cg == 0) s_lds[n - 1] = scale * dot;
-            *reinterpret_cast<u32x4 *>(const_cast<char *>(kbase) + (size_t)(n - 1) * TL::ROW_BYTES) = nraw;
-        }
-    }
-    __syncthreads();
-
-    const float sv = tid < n ? s_lds[tid] : -INFINITY;
-    const float m = block_max(sv, red);
-    const float l = block_sum(tid < n ? expf(sv - m) : 0.f, red);
-    const size_t row = (size_t)b * k + j;
-    if (tid < n) scores[row * T + t0 + tid] = sv;
-    if (tid == 0) stats[row * n_cs + chunk] = make_float2(m, l);
-}
-
 // ---------------------------------------------------------------------------------------------------------
 // Value kernel: out[b][h] = sum_t p_c[t] * V[b][h][t], c = cluster of h.  grid = (n_cp, H, B).
 //
@@ -243,15 +115,13 @@ __global__ __launch_bounds__(kBlock) void score_kernel(const char *__restrict__ 
 // lines): twice the workgroups without partial rows to add up afterwards -- for head counts that are too small
 // for one workgroup per head and would otherwise pay a combine launch.  grid = (n_cp, H * DS, B).
 template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND, int DS>
-__global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__ v,
-                                                        const int32_t *__restrict__ h2c,
-                                                        const int32_t *__restrict__ rep, int H, int k, int T,
-                                                        int T_cap, int n_cs, int cp, int n_cp,
-                                                        const float *__restrict__ scores,
-                                                        const float2 *__restrict__ stats,
-                                                        float *__restrict__ partial, float *__restrict__ out,
-                                                        float *__restrict__ probs_out,
-                                                        const char *__restrict__ v_new)
+__device__ __forceinline__ void value_block(const char *__restrict__ v, const int32_t *__restrict__ h2c,
+                                            const int32_t *__restrict__ rep, int H, int k, int T, int T_cap,
+                                            int n_rec, int cp, int n_cp,
+                                            const float *__restrict__ scores, const float2 *__restrict__ stats,
+                                            float *__restrict__ partial, float *__restrict__ out,
+                                            float *__restrict__ probs_out, const char *__restrict__ v_new,
+                                            int split, int hy, int b)
 {
     using TL = VTile<BF16, DS>;
     __shared__ float p_lds[NW][TL::BATCH];
@@ -260,7 +130,7 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
     const int cg = lane % TL::LPR, rg = lane / TL::LPR;
-    const int split = blockIdx.x, h = blockIdx.y / DS, dpart = blockIdx.y % DS, b = blockIdx.z;
+    const int h = hy / DS, dpart = hy % DS;
     const int t0 = split * cp;
     const int n_all = min(T, t0 + cp) - t0;
     const bool has_new = APPEND && split == n_cp - 1;        // this chunk ends with the token being decoded
@@ -309,12 +179,12 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
 #pragma unroll
     for (int j = 0; j < NB; ++j) request_s(buf[j], j);
 
-    const float2 *st = stats + crow * n_cs;
+    const float2 *st = stats + crow * n_rec;
     float m = -INFINITY;
-    for (int i = lane; i < n_cs; i += 64) m = fmaxf(m, st[i].x);
+    for (int i = lane; i < n_rec; i += 64) m = fmaxf(m, st[i].x);
     const float M = wave_max(m);
     float l = 0.f;
-    for (int i = lane; i < n_cs; i += 64) l += st[i].y * expf(st[i].x - M);
+    for (int i = lane; i < n_rec; i += 64) l += st[i].y * expf(st[i].x - M);
     const float inv = 1.0f / wave_sum(l);
 
     float acc[TL::EPL];
@@ -391,6 +261,141 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
     }
 }
 
+template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND, int DS>
+__global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__ v,
+                                                        const int32_t *__restrict__ h2c,
+                                                        const int32_t *__restrict__ rep, int H, int k, int T,
+                                                        int T_cap, int n_rec, int cp, int n_cp,
+                                                        const float *__restrict__ scores,
+                                                        const float2 *__restrict__ stats,
+                                                        float *__restrict__ partial, float *__restrict__ out,
+                                                        float *__restrict__ probs_out,
+                                                        const char *__restrict__ v_new)
+{
+    value_block<BF16, IDENT, NW, NB, WRITE_P, APPEND, DS>(v, h2c, rep, H, k, T, T_cap, n_rec, cp, n_cp, scores,
+                                                          stats, partial, out, probs_out, v_new, blockIdx.x,
+                                                          blockIdx.y, blockIdx.z);
+}
+
+// ---------------------------------------------------------------------------------------------------------
+// Score kernel: s[b][j][t] = scale * q[b][rep(b,j)] . Kc[b][j][t], plus (max, sum of exp) records for the value
+// kernel's exact merge.  grid = (n_cs, k, B): a workgroup takes a chunk of cs tokens of one cluster's key stream.
+//
+// A wave owns every NW-th batch of BATCH consecutive rows of its chunk, keeps NB batches in flight and refills a
+// buffer right after it has consumed it.  After the 16-lane row sums every lane of a lane group holds the dot
+// products of the group's kUnroll rows; lane cg < kUnroll keeps the one of load u = cg, so the first kUnroll lanes
+// of every group own one score each (row rg + cg * RPW of the batch): BATCH scores per wave, written as one
+// 128-byte (bf16 rows) piece of the score row.  The softmax statistics are carried per lane (running maximum and
+// sum of exponentials over the scores the lane has seen) and reduced once over the wave at the end: one
+// (max, sum-exp) record per wave (n_cs * NW per cluster), no workgroup barrier anywhere, no LDS.
+// APPEND: the last position, T-1, is the token being decoded: its key is not in the cache yet.  The workgroup of
+// the last chunk takes it from k_new [B,H,d] (row of the representative), scores it, and writes it to the cache,
+// so that growing the cache costs no launch of its own.
+// ---------------------------------------------------------------------------------------------------------
+template <bool BF16, bool IDENT, bool APPEND, int NW, int NB>
+__global__ __launch_bounds__(NW * 64) void score_kernel(const char *__restrict__ q, const char *__restrict__ kc,
+                                                        const int32_t *__restrict__ rep, int H, int k, int T,
+                                                        int Tc_cap, float scale, int cs, int n_cs,
+                                                        float *__restrict__ scores, float2 *__restrict__ stats,
+                                                        const char *__restrict__ k_new)
+{
+    using TL = Tile<BF16>;
+    const int chunk = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, w = tid >> 6;
+    const int cg = lane % TL::LPR, rg = lane / TL::LPR;
+    const int t0 = chunk * cs;
+    const int n_all = min(T, t0 + cs) - t0;                   // >= 1 by construction of n_cs
+    const bool has_new = APPEND && chunk == n_cs - 1;         // this chunk ends with the token being decoded
+    const int n = has_new ? n_all - 1 : n_all;                // rows that are in the cache already (may be 0)
+    const int n_batches = (n + TL::BATCH - 1) / TL::BATCH;
+    const int n_it = n_batches > w ? (n_batches - w + NW - 1) / NW : 0;
+
+    const char *kbase = kc + (((size_t)b * k + j) * Tc_cap + t0) * TL::ROW_BYTES;
+    const unsigned int lane_off = cg * 16;
+    u32x4 buf[NB][kUnroll];
+    auto clamp_row = [&](int row) { return APPEND ? max(min(row, n - 1), 0) : min(row, n - 1); };
+    auto request = [&](u32x4 (&bt)[kUnroll], int it) {
+        const int r0 = (it * NW + w) * TL::BATCH + rg;
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u)
+            bt[u] = stream16(kbase + ((unsigned int)clamp_row(r0 + u * TL::RPW) * TL::ROW_BYTES + lane_off));
+    };
+#pragma unroll
+    for (int i = 0; i < NB; ++i) request(buf[i], i);
+
+    int r = IDENT ? j : rep[(size_t)b * k + j];
+    if (r < 0) return;                       // unused cluster slot (same decision for every wave of the chunk)
+    r = min(r, H - 1);
+    float qf[TL::EPL];
+    {
+        const u32x4 qraw = *reinterpret_cast<const u32x4 *>(q + ((size_t)b * H + r) * TL::ROW_BYTES + lane_off);
+        unpack(qraw, qf);
+    }
+    float *srow = scores + ((size_t)b * k + j) * T + t0;
+    float m_run = -INFINITY, l_run = 0.f;
+    // The stored score is the ROUNDED product: the statistics below and the value kernel must both start from
+    // that value (a multiply fused into the subtraction of the running maximum would use the unrounded one,
+    // and with scores of magnitude 10^3 the difference reaches 1e-4 of a probability).
+    auto scaled = [&](float x) {
+#pragma clang fp contract(off)
+        return scale * x;
+    };
+    auto see = [&](float sv) {               // running softmax statistics of this lane
+        const float m_new = fmaxf(m_run, sv);
+        l_run = l_run * __expf(m_run - m_new) + __expf(sv - m_new);
+        m_run = m_new;
+    };
+
+    for (int it0 = 0; it0 < n_it; it0 += NB) {
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int it = it0 + i;
+            float mine = 0.f;
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                float f[TL::EPL];
+                unpack(buf[i][u], f);
+                float dot = 0.f;
+#pragma unroll
+                for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
+                dot = row_sum<BF16>(dot);
+                mine = cg == u ? dot : mine;
+            }
+            request(buf[i], it + NB);
+            const int tl = (it * NW + w) * TL::BATCH + rg + cg * TL::RPW;
+            if (cg < kUnroll && tl < n) {
+                const float sv = scaled(mine);
+                srow[tl] = sv;
+                see(sv);
+            }
+        }
+    }
+    if (APPEND) {
+        if (has_new && w == 0 && rg == 0) {      // one lane group: the new key row of the representative
+            const u32x4 nraw = *reinterpret_cast<const u32x4 *>(k_new + ((size_t)b * H + r) * TL::ROW_BYTES + lane_off);
+            float f[TL::EPL];
+            unpack(nraw, f);
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
+            dot = row_sum<BF16>(dot);
+            if (cg == 0) {
+                const float sv = scaled(dot);
+                srow[n] = sv;
+                see(sv);
+            }
+            *reinterpret_cast<u32x4 *>(const_cast<char *>(kbase) + ((unsigned int)n * TL::ROW_BYTES + lane_off)) = nraw;
+        }
+    }
+    // one record per wave: lanes without scores carry (-inf, 0) and drop out of the merge
+    const float M = wave_max(m_run);
+    const float L = wave_sum(m_run == -INFINITY ? 0.f : l_run * __expf(m_run - M));
+    if (lane == 0) {
+        stats[((size_t)b * k + j) * ((size_t)n_cs * NW) + (size_t)chunk * NW + w] = make_float2(M, L);
+    }
+}
+
 // Sum of the partial rows of every head in chunk order.  grid = (B*H), 128 threads.
 __global__ __launch_bounds__(kHeadDim) void combine_kernel(const float *__restrict__ partial, int n_cp,
                                                            float *__restrict__ out)
@@ -429,29 +434,30 @@ struct Workspace {
     }
 };
 
-// Launches go through hipExtLaunchKernelGGL so that a caller who profiles can have the runtime stamp the begin
-// and the end of the kernel itself into a pair of events (both NULL for an ordinary launch).
+// Launches carry the optional pair of events that the runtime stamps with the begin and the end of the kernel
+// itself (both NULL for an ordinary launch), for callers who profile.
 template <bool BF16, bool IDENT>
 int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap,
                  float scale, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev, hipStream_t stream,
                  const void *k_new)
 {
+    const dim3 grid(pl.n_cs, k, B), block(kScoreWaves * 64);
+    const char *qc = static_cast<const char *>(q), *kcc = static_cast<const char *>(kc);
     if (!IDENT && k_new != nullptr)
-        hipExtLaunchKernelGGL((score_kernel<BF16, false, true>), dim3(pl.n_cs, k, B), dim3(kBlock), 0, stream, ev.start,
-                              ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc), rep, H, k, T,
-                              Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats, static_cast<const char *>(k_new));
-    else
-        hipExtLaunchKernelGGL((score_kernel<BF16, IDENT, false>), dim3(pl.n_cs, k, B), dim3(kBlock), 0, stream,
-                              ev.start, ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc), rep, H,
-                              k, T, Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats,
-                              static_cast<const char *>(nullptr));
-    return (int)hipGetLastError();
+        return (int)launch_kernel(score_kernel<BF16, false, true, kScoreWaves, kScoreBatches>, grid, block, 0, stream, ev,
+                                  qc, kcc, rep, H, k, T, Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats,
+                                  static_cast<const char *>(k_new));
+    return (int)launch_kernel(score_kernel<BF16, IDENT, false, kScoreWaves, kScoreBatches>, grid, block, 0, stream, ev, qc,
+                              kcc, rep, H, k, T, Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats, nullptr);
 }
 
 // A merge of the partial rows inside the value kernel (last workgroup of a head, found through a device-scope
 // arrival counter) was measured and dropped: with __threadfence() in every workgroup the kernel ran 10x slower
 // (L2 write-back + invalidate per fence across 8 XCDs), and with fence-free device-scope stores/loads it was
-// still slower than the separate combine launch at every chunk count tried.
+// still slower than the separate combine launch at every chunk count tried.  So was a single launch of both
+// phases (score workgroups first in the grid, value workgroups prefetching V and waiting on per-cluster
+// device-scope counters): 67 us against 55 us per LLaMa-7B layer -- cross-XCD flag traffic costs more than the
+// 2.5 us of a second launch.
 template <bool BF16, bool IDENT, int NW, int NB, int DS>
 int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
@@ -459,35 +465,28 @@ int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
 {
     // the copy of the probabilities (tests, inspection) lives in an instantiation of its own so that the
     // production kernel has no store inside its streaming loop; so does the variant that appends the new token
-    const char *no_new = nullptr;
+    const dim3 grid(pl.n_cp, H * DS, B), block(NW * 64);
+    const char *vc = static_cast<const char *>(v);
+    hipError_t e;
     if (!IDENT && v_new != nullptr)
-        hipExtLaunchKernelGGL((value_kernel<BF16, false, NW, NB, false, true, DS>), dim3(pl.n_cp, H * DS, B), dim3(NW * 64), 0,
-                              stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
-                              pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
-                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out,
-                              static_cast<const char *>(v_new));
+        e = launch_kernel(value_kernel<BF16, false, NW, NB, false, true, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H, k,
+                          T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out,
+                          static_cast<const char *>(v_new));
     else if (probs_out != nullptr)
-        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, true, false, DS>), dim3(pl.n_cp, H * DS, B), dim3(NW * 64), 0,
-                              stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
-                              pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
-                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out, no_new);
+        e = launch_kernel(value_kernel<BF16, IDENT, NW, NB, true, false, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H, k,
+                          T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out, nullptr);
     else
-        hipExtLaunchKernelGGL((value_kernel<BF16, IDENT, NW, NB, false, false, DS>), dim3(pl.n_cp, H * DS, B), dim3(NW * 64), 0,
-                              stream, ev.start, ev.stop, 0, static_cast<const char *>(v), h2c, rep, H, k, T, T_cap,
-                              pl.n_cs, pl.cp, pl.n_cp, static_cast<const float *>(w.scores),
-                              static_cast<const float2 *>(w.stats), w.partial, out, probs_out, no_new);
-    hipError_t e = hipGetLastError();
+        e = launch_kernel(value_kernel<BF16, IDENT, NW, NB, false, false, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H,
+                          k, T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out, nullptr);
     if (e != hipSuccess) return (int)e;
-    if (members != nullptr) {
+    if (members != nullptr)
         // one launch both adds the partial rows (n_cp = 1: the staged row itself) and hands them to the members
-        combine_members_kernel<<<dim3(members->n_heads, B), kHeadDim, 0, stream>>>(
-            pl.n_cp == 1 ? out : w.partial, pl.n_cp, members->head_to_cluster, members->n_heads, H,
-            members->out_members);
-        return (int)hipGetLastError();
-    }
-    if (pl.n_cp == 1) return (int)e;
-    combine_kernel<<<dim3(B * H), kHeadDim, 0, stream>>>(w.partial, pl.n_cp, out);
-    return (int)hipGetLastError();
+        return (int)launch_kernel(combine_members_kernel, dim3(members->n_heads, B), dim3(kHeadDim), 0, stream,
+                                  KernelEvents(), pl.n_cp == 1 ? out : w.partial, pl.n_cp, members->head_to_cluster,
+                                  members->n_heads, H, members->out_members);
+    if (pl.n_cp == 1) return (int)hipSuccess;
+    return (int)launch_kernel(combine_kernel, dim3(B * H), dim3(kHeadDim), 0, stream, KernelEvents(), w.partial, pl.n_cp,
+                              out);
 }
 
 template <bool BF16, bool IDENT>
@@ -498,22 +497,13 @@ int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, i
     // Workgroup shape (measured on MI355X): eight waves with one batch in flight each are 1-6 % faster than
     // four waves with two batches up to a few thousand tokens per workgroup; on long chunks four waves with
     // two batches are ~1.5 % ahead.
-    int nw = pl.cp >= 4096 ? 4 : 8;
-    int nb = pl.cp >= 4096 ? 2 : 1;
-#ifdef CHAI_TUNING
-    if (getenv("CHAI_NW")) nw = atoi(getenv("CHAI_NW"));
-    if (getenv("CHAI_NB")) nb = atoi(getenv("CHAI_NB"));
-    if (nw == 4 && nb == 3)
-        return values_launch<BF16, IDENT, 4, 3, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
-    if (nw == 16 && nb == 1)
-        return values_launch<BF16, IDENT, 16, 1, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
-#endif
+    const bool long_chunks = pl.cp >= 4096;
     if (pl.ds == 2) {
-        if (nw == 4 && nb == 2)
+        if (long_chunks)
             return values_launch<BF16, IDENT, 4, 2, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
         return values_launch<BF16, IDENT, 8, 1, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
     }
-    if (nw == 4 && nb == 2)
+    if (long_chunks)
         return values_launch<BF16, IDENT, 4, 2, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
     return values_launch<BF16, IDENT, 8, 1, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
 }
@@ -525,10 +515,12 @@ size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 DecodePlan make_decode_plan(int B, int H, int k, int T)
 {
     DecodePlan pl;
-    // score chunk: the largest of 256/128/64 tokens that still gives >= 1024 workgroups (4 per CU)
-    pl.cs = 64;
-    for (int c : {256, 128}) {
-        if ((long long)B * k * ((T + c - 1) / c) >= 1024) { pl.cs = c; break; }
+    // Score chunk (measured on MI355X on the LLaMa-7B/33B, OPT-66B and 32k-context shapes): the largest of
+    // 2048/1024/512 tokens that still gives one workgroup per CU; smaller problems take 256 (one round of the
+    // workgroup's waves with both batches in flight).
+    pl.cs = 256;
+    for (int c : {2048, 1024, 512}) {
+        if ((long long)B * k * ((T + c - 1) / c) >= 256) { pl.cs = c; break; }
     }
     // value chunk (measured on MI355X at T = 2048): with >= 384 heads one workgroup per head -- whole row of
     // the cache, no partial rows, no combine launch -- is fastest (416 heads: 39 us against 41-44 us split);
@@ -547,21 +539,16 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
         if (want > most) want = most;
         pl.cp = (int)(((T + want - 1) / want + 127) / 128 * 128);
     }
-#ifdef CHAI_TUNING
-    // experiment hooks, compiled only into tuning builds
-    if (const char *e = getenv("CHAI_CS")) pl.cs = atoi(e);
-    if (const char *e = getenv("CHAI_CP")) pl.cp = atoi(e);
-    if (const char *e = getenv("CHAI_DS")) pl.ds = atoi(e);
-#endif
     pl.n_cs = (T + pl.cs - 1) / pl.cs;
+    pl.n_rec = pl.n_cs * kScoreWaves;
     pl.n_cp = (T + pl.cp - 1) / pl.cp;
 
     // Region sizes are upper bounds over every chunking the rules above can pick (smallest chunks), so the
     // total grows monotonically with T: a workspace sized for the cache capacity serves every shorter context.
-    const size_t max_n_cs = (size_t)(T + 63) / 64, max_n_cp = (size_t)(T + 127) / 128;
+    const size_t max_n_rec = (size_t)(T + 255) / 256 * kScoreWaves, max_n_cp = (size_t)(T + 127) / 128;
     size_t off = 0;
     pl.off_scores = off;  off = align_up(off + (size_t)B * k * T * sizeof(float), 256);
-    pl.off_stats = off;   off = align_up(off + (size_t)B * k * max_n_cs * sizeof(float2), 256);
+    pl.off_stats = off;   off = align_up(off + (size_t)B * k * max_n_rec * sizeof(float2), 256);
     pl.off_partial = off; off = align_up(off + (size_t)B * H * max_n_cp * kHeadDim * sizeof(float), 256);
     pl.off_rows = off;    off = align_up(off + (size_t)B * H * kHeadDim * sizeof(float), 256);
     pl.bytes = off;

@@ -292,9 +292,8 @@ int assignment_slices(int H, int k)
 int launch_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int dtype, int64_t qs, int64_t ks,
                           float scale, float *feat, hipStream_t stream)
 {
-    feature_kernel<<<dim3(H, B), 64, 0, stream>>>(q5, k5, H, n_tok, dtype == CHAI_BF16 ? 1 : 0, (long long)qs,
-                                                  (long long)ks, (double)scale, feat);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(feature_kernel, dim3(H, B), dim3(64), 0, stream, KernelEvents(), q5, k5, H, n_tok,
+                              dtype == CHAI_BF16 ? 1 : 0, (long long)qs, (long long)ks, (double)scale, feat);
 }
 
 size_t assign_clusters_lds_bytes(int H, int F, int k)
@@ -315,9 +314,9 @@ int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const 
                            int32_t *h2c, int32_t *rep, int32_t *ncl, int32_t *iters, hipStream_t stream)
 {
     const size_t copy = kmeans_feature_copy_bytes(H, F, k);
-    kmeans_kernel<<<dim3(B), kBlock, assign_clusters_lds_bytes(H, F, k) + copy, stream>>>(
-        feat, H, F, k, init_heads, max_iter, assignment_slices(H, k), copy != 0 ? 1 : 0, h2c, rep, ncl, iters);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(kmeans_kernel, dim3(B), dim3(kBlock), assign_clusters_lds_bytes(H, F, k) + copy, stream,
+                              KernelEvents(), feat, H, F, k, init_heads, max_iter, assignment_slices(H, k),
+                              copy != 0 ? 1 : 0, h2c, rep, ncl, iters);
 }
 
 size_t cluster_error_lds_bytes(int H, int F, int k)
@@ -328,9 +327,8 @@ size_t cluster_error_lds_bytes(int H, int F, int k)
 int launch_cluster_error(const float *feat, const int32_t *h2c, int B, int H, int F, int k, double *sse,
                          int32_t *rep_out, hipStream_t stream)
 {
-    cluster_error_kernel<<<dim3(B), kBlock, cluster_error_lds_bytes(H, F, k), stream>>>(feat, h2c, H, F, k, sse,
-                                                                                        rep_out);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(cluster_error_kernel, dim3(B), dim3(kBlock), cluster_error_lds_bytes(H, F, k), stream,
+                              KernelEvents(), feat, h2c, H, F, k, sse, rep_out);
 }
 
 }  // namespace chai

@@ -518,8 +518,8 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     _Float16 *vt = reinterpret_cast<_Float16 *>(ws);
     const int n_qt = (Tq + kQTile - 1) / kQTile;
 
-    vt_kernel<<<dim3(Tp / kKTile, H, B), 256, 0, stream>>>(static_cast<const char *>(v), H, T_cap, n_keys, Tp, vt);
-    hipError_t e = hipGetLastError();
+    hipError_t e = launch_kernel(vt_kernel, dim3(Tp / kKTile, H, B), dim3(256), 0, stream, KernelEvents(),
+                                 static_cast<const char *>(v), H, T_cap, n_keys, Tp, vt);
     if (e != hipSuccess) return (int)e;
     static DeviceFlags lds_ident, lds_clustered;
     e = allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<true>), prefill_lds_bytes(true), lds_ident);
@@ -533,23 +533,16 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
     if ((long long)n_pairs * max_groups * B > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     const unsigned int n_wg = (unsigned int)n_pairs * (unsigned int)max_groups * (unsigned int)B;
     if (identity) {
-        hipExtLaunchKernelGGL(prefill_kernel<true>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(true), stream, ev.start,
-                              ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc),
-                              static_cast<const _Float16 *>(vt), static_cast<const int32_t *>(nullptr),
-                              static_cast<const int32_t *>(nullptr), static_cast<const int32_t *>(nullptr), H, k, Tq,
-                              q_start, Tc_cap, Tp, n_qt_arg, max_groups, scale, out);
-        return (int)hipGetLastError();
+        return (int)launch_kernel(prefill_kernel<true>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(true), stream, ev,
+                                  static_cast<const char *>(q), static_cast<const char *>(kc), vt, nullptr, nullptr,
+                                  nullptr, H, k, Tq, q_start, Tc_cap, Tp, n_qt_arg, max_groups, scale, out);
     }
-    prefill_plan_kernel<<<dim3(B), 256, (size_t)(H + 2 * k) * sizeof(int32_t), stream>>>(h2c, rep, H, k, kGroup, max_groups,
-                                                                                        groups, n_groups);
-    e = hipGetLastError();
+    e = launch_kernel(prefill_plan_kernel, dim3(B), dim3(256), (size_t)(H + 2 * k) * sizeof(int32_t), stream,
+                      KernelEvents(), h2c, rep, H, k, kGroup, max_groups, groups, n_groups);
     if (e != hipSuccess) return (int)e;
-    hipExtLaunchKernelGGL(prefill_kernel<false>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(false), stream, ev.start,
-                          ev.stop, 0, static_cast<const char *>(q), static_cast<const char *>(kc),
-                          static_cast<const _Float16 *>(vt), rep, static_cast<const int32_t *>(groups),
-                          static_cast<const int32_t *>(n_groups), H, k, Tq, q_start, Tc_cap, Tp, n_qt_arg, max_groups, scale,
-                          out);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(prefill_kernel<false>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(false), stream, ev,
+                              static_cast<const char *>(q), static_cast<const char *>(kc), vt, rep, groups, n_groups, H, k,
+                              Tq, q_start, Tc_cap, Tp, n_qt_arg, max_groups, scale, out);
 }
 
 }  // namespace chai

@@ -201,9 +201,8 @@ double mfma_probe_flops(int rounds)
 
 int launch_mfma_probe(const void *buf, size_t bytes, int rounds, float *sink, const KernelEvents &ev, hipStream_t stream)
 {
-    hipExtLaunchKernelGGL(mfma_probe_kernel, dim3(kProbeBlocks), dim3(kJBlock), 0, stream, ev.start, ev.stop, 0,
-                          static_cast<const u32x4 *>(buf), (unsigned long long)(bytes / 16), rounds, sink);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(mfma_probe_kernel, dim3(kProbeBlocks), dim3(kJBlock), 0, stream, ev,
+                              static_cast<const u32x4 *>(buf), (unsigned long long)(bytes / 16), rounds, sink);
 }
 
 int launch_project_qk(const void *x, const void *w_q, const void *w_k, const int32_t *rep, int B, int H, int k, int Tn,
@@ -215,11 +214,10 @@ int launch_project_qk(const void *x, const void *w_q, const void *w_k, const int
     if (attr != hipSuccess) return (int)attr;
     const int n_mt = (Tn + kJTok - 1) / kJTok;
     if ((long long)n_mt * k * B > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
-    hipExtLaunchKernelGGL(project_kernel, dim3((unsigned int)n_mt * k * B), dim3(kJBlock), kJLdsBytes, stream, ev.start,
-                          ev.stop, 0, static_cast<const char *>(x), static_cast<const char *>(w_q),
-                          static_cast<const char *>(w_k), rep, H, k, Tn, D, n_mt, static_cast<char *>(q_out),
-                          static_cast<char *>(k_compact), pos0, Tc_cap);
-    return (int)hipGetLastError();
+    return (int)launch_kernel(project_kernel, dim3((unsigned int)n_mt * k * B), dim3(kJBlock), kJLdsBytes, stream, ev,
+                              static_cast<const char *>(x), static_cast<const char *>(w_q), static_cast<const char *>(w_k),
+                              rep, H, k, Tn, D, n_mt, static_cast<char *>(q_out), static_cast<char *>(k_compact), pos0,
+                              Tc_cap);
 }
 
 }  // namespace chai
