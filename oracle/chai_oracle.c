@@ -18,7 +18,10 @@
  * an independent Lloyd implementation with the same start, index gathers,
  * the shared-value ablation against dense attention of the representative,
  * the nearest-to-mean representative against hand-worked cases and numpy,
- * the representatives' projections against a library contraction.
+ * the representatives' projections against a library contraction, the
+ * 8-bit floating point codes against the format's published values, a
+ * library's conversion and brute-force nearest search, quantised attention
+ * against a library softmax/matmul on dequantised tensors.
  * Unpinned: no function of this file.  (How well clustered attention
  * approximates dense attention on trained models is not computed here at
  * all; it needs weights and datasets.)
@@ -614,6 +617,183 @@ int chai_oracle_kmeans(const float *feat, int B, int H, int F, int k, const int3
         if (sse) sse[b] = partition_error(X, head_to_cluster + (int64_t)b * H, H, F, k, centre);
     }
     free(centre); free(dmin); free(assign); free(prev); free(count); free(label);
+    return 0;
+}
+
+/*
+ * ---------------------------------------------------------------------
+ * Quantised key/value caches (Section 2, related work: quantisation of
+ * the K,V cache is orthogonal to clustering heads and can be combined with
+ * it).  The paper gives no format; the reading used here:
+ *
+ *  - elements are 8-bit floating point E4M3 as defined by the OCP 8-bit
+ *    floating point specification: 1 sign, 4 exponent bits (bias 7),
+ *    3 mantissa bits, subnormals, no infinities, S.1111.111 = NaN, largest
+ *    finite magnitude 448;
+ *  - one fp32 scale per cached row (one token of one key or value stream):
+ *    amax = max_i |x_i|, scale = amax / 448, code_i = nearest E4M3 value
+ *    (ties to even) of x_i * (448 / amax), computed in fp32 -- the
+ *    precision the device uses, because these steps decide integer codes;
+ *    an all-zero row has scale 0 and codes 0;
+ *  - the dequantised element is decode(code_i) * scale, and attention over a
+ *    quantised cache is, by definition, the plain attention over the
+ *    dequantised cache ("dequantise, then attend").
+ * ---------------------------------------------------------------------
+ */
+
+/* value of one E4M3 code (NaN for 0x7f / 0xff) */
+double chai_oracle_e4m3_decode(int code)
+{
+    int sign = (code >> 7) & 1, e = (code >> 3) & 15, m = code & 7;
+    double mag;
+    if (e == 15 && m == 7) return NAN;
+    if (e == 0) mag = ldexp((double)m / 8.0, 1 - 7);          /* subnormal: 0.mmm * 2^(1-bias) */
+    else mag = ldexp(1.0 + (double)m / 8.0, e - 7);          /* normal: 1.mmm * 2^(e-bias)    */
+    return sign ? -mag : mag;
+}
+
+/*
+ * nearest E4M3 code of a finite y, ties to the even mantissa, magnitudes
+ * above 448 saturate to 448 (NaN gives the NaN code)
+ */
+int chai_oracle_e4m3_encode(float y)
+{
+    if (isnan(y)) return 0x7f;
+    int sign = signbit(y) ? 0x80 : 0;
+    double a = fabs((double)y);
+    if (a >= 448.0) return sign | 0x7e;
+    if (a == 0.0) return sign;
+    int ex;
+    frexp(a, &ex);                       /* a = f * 2^ex, 0.5 <= f < 1  ->  floor(log2 a) = ex - 1 */
+    int e = ex - 1;
+    if (e < -6) e = -6;                  /* below the smallest normal the spacing stays 2^-9 */
+    double step = ldexp(1.0, e - 3);     /* spacing of representable values around a */
+    double r = nearbyint(a / step);      /* default rounding mode: to nearest, ties to even */
+    double val = r * step;               /* may have moved up into the next binade: still representable */
+    if (val == 0.0) return sign;
+    int code;
+    if (val < ldexp(1.0, -6)) {
+        code = (int)(val / ldexp(1.0, -9));              /* subnormal: mantissa counts steps of 2^-9 */
+    } else {
+        frexp(val, &ex);
+        int E = ex - 1 + 7;
+        int M = (int)(val / ldexp(1.0, ex - 1) * 8.0) - 8;
+        code = (E << 3) | M;
+    }
+    return sign | code;
+}
+
+/*
+ * Quantise n_rows rows of d elements (dtype fp32 or bf16) to E4M3 codes with
+ * one fp32 scale per row, by the rule in the header above.  The three fp32
+ * operations (amax / 448, 448 / amax, x * that) are single IEEE operations.
+ */
+int chai_oracle_quantize_rows(const void *x, int64_t n_rows, int d, int dtype, uint8_t *codes, float *scales)
+{
+    if (!x || !codes || !scales) return 1;
+    if (n_rows < 0 || d < 1) return 2;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return 3;
+    for (int64_t r = 0; r < n_rows; ++r) {
+        float amax = 0.0f;
+        for (int i = 0; i < d; ++i) {
+            float v = fabsf((float)load_elem(x, r * d + i, dtype));
+            if (v > amax) amax = v;
+        }
+        if (amax == 0.0f) {
+            scales[r] = 0.0f;
+            for (int i = 0; i < d; ++i) codes[r * d + i] = 0;
+            continue;
+        }
+        float scale = amax / 448.0f;
+        float inv = 448.0f / amax;
+        scales[r] = scale;
+        for (int i = 0; i < d; ++i) {
+            float yc = (float)load_elem(x, r * d + i, dtype) * inv;
+            if (yc > 448.0f) yc = 448.0f;
+            if (yc < -448.0f) yc = -448.0f;
+            codes[r * d + i] = (uint8_t)chai_oracle_e4m3_encode(yc);
+        }
+    }
+    return 0;
+}
+
+/* dequantised rows in double: decode(code) * scale, exactly */
+int chai_oracle_dequantize_rows(const uint8_t *codes, const float *scales, int64_t n_rows, int d, double *x)
+{
+    if (!codes || !scales || !x) return 1;
+    if (n_rows < 0 || d < 1) return 2;
+    for (int64_t r = 0; r < n_rows; ++r)
+        for (int i = 0; i < d; ++i)
+            x[r * d + i] = chai_oracle_e4m3_decode(codes[r * d + i]) * (double)scales[r];
+    return 0;
+}
+
+/*
+ * One decode step of clustered-head attention over quantised caches: the
+ * definition of chai_oracle_clustered_decode with every key and value
+ * element replaced by its dequantised value decode(code) * scale_of_its_row
+ * (dequantise, then attend).  k8, v8 [B,H,T_cap,d] codes of the FULL caches,
+ * kscale, vscale [B,H,T_cap]; q [B,H,d] in `dtype`.
+ */
+int chai_oracle_clustered_decode_q8(const void *q, const uint8_t *k8, const float *kscale, const uint8_t *v8,
+                                    const float *vscale, const int32_t *head_to_cluster,
+                                    const int32_t *rep_heads, int B, int H, int k, int T, int T_cap, int d,
+                                    int dtype, double scale, double *out, double *probs)
+{
+    if (!q || !k8 || !kscale || !v8 || !vscale || !head_to_cluster || !rep_heads || !out) return 1;
+    if (B < 0 || H < 1 || k < 1 || k > H || T < 1 || T > T_cap || d < 1) return 2;
+    if (dtype != ORC_F32 && dtype != ORC_BF16) return 3;
+    for (int b = 0; b < B; ++b)
+        for (int h = 0; h < H; ++h) {
+            int c = head_to_cluster[(int64_t)b * H + h];
+            if (c < 0 || c >= k) return 2;
+            int r = rep_heads[(int64_t)b * k + c];
+            if (r < 0 || r >= H) return 2;
+        }
+    double *p_all = (double *)malloc(sizeof(double) * (size_t)B * k * T + 8);
+    if (!p_all) return 4;
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        for (int j = 0; j < k; ++j) {
+            double *p = p_all + ((int64_t)b * k + j) * T;
+            int r = rep_heads[(int64_t)b * k + j];
+            if (r < 0 || r >= H) {
+                for (int t = 0; t < T; ++t) p[t] = NAN;
+                continue;
+            }
+            double *s = (double *)malloc(sizeof(double) * (size_t)T);
+            int64_t qoff = ((int64_t)b * H + r) * d;
+            int64_t row0 = ((int64_t)b * H + r) * (int64_t)T_cap;
+            for (int t = 0; t < T; ++t) {
+                double acc = 0.0;
+                for (int i = 0; i < d; ++i) {
+                    double kd = chai_oracle_e4m3_decode(k8[(row0 + t) * d + i]) * (double)kscale[row0 + t];
+                    acc += load_elem(q, qoff + i, dtype) * kd;
+                }
+                s[t] = scale * acc;
+            }
+            softmax_row(s, T, p);
+            free(s);
+        }
+    }
+#pragma omp parallel for collapse(2) schedule(dynamic)
+    for (int b = 0; b < B; ++b) {
+        for (int h = 0; h < H; ++h) {
+            int c = head_to_cluster[(int64_t)b * H + h];
+            const double *p = p_all + ((int64_t)b * k + c) * T;
+            int64_t row0 = ((int64_t)b * H + h) * (int64_t)T_cap;
+            for (int i = 0; i < d; ++i) {
+                double acc = 0.0;
+                for (int t = 0; t < T; ++t) {
+                    double vd = chai_oracle_e4m3_decode(v8[(row0 + t) * d + i]) * (double)vscale[row0 + t];
+                    acc += p[t] * vd;
+                }
+                out[((int64_t)b * H + h) * d + i] = acc;
+            }
+        }
+    }
+    if (probs) memcpy(probs, p_all, sizeof(double) * (size_t)B * k * T);
+    free(p_all);
     return 0;
 }
 

@@ -49,6 +49,13 @@ def _configure(L: ctypes.CDLL) -> ctypes.CDLL:
     L.chai_oracle_project_qk.argtypes = [vp, vp, vp, i32p, ci, ci, ci, ci, ci, ci, ci, vp, vp]
     L.chai_oracle_compact_kcache.argtypes = [vp, i32p, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
     L.chai_oracle_append_kv.argtypes = [vp, vp, i32p, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci]
+    L.chai_oracle_e4m3_decode.argtypes = [ci]
+    L.chai_oracle_e4m3_decode.restype = cd
+    L.chai_oracle_e4m3_encode.argtypes = [ctypes.c_float]
+    L.chai_oracle_e4m3_encode.restype = ci
+    L.chai_oracle_quantize_rows.argtypes = [vp, i64, ci, ci, vp, vp]
+    L.chai_oracle_dequantize_rows.argtypes = [vp, vp, i64, ci, vp]
+    L.chai_oracle_clustered_decode_q8.argtypes = [vp, vp, vp, vp, vp, i32p, i32p, ci, ci, ci, ci, ci, ci, ci, cd, vp, vp]
     return L
 
 
@@ -285,3 +292,55 @@ def append_kv(k_new, v_new, rep_heads, k_compact, v_cache, pos):
     rc = lib().chai_oracle_append_kv(_p(k_new), _p(v_new), _p(rep), _p(k_compact), _p(v_cache), B, H, k, int(pos),
                                      k_compact.shape[2], v_cache.shape[2], d, dt)
     _check(rc, "append_kv")
+
+
+def e4m3_decode(code: int) -> float:
+    """Value of one 8-bit E4M3 code (NaN for 0x7f / 0xff)."""
+    return float(lib().chai_oracle_e4m3_decode(int(code)))
+
+
+def e4m3_encode(y: float) -> int:
+    """Nearest E4M3 code of the fp32 value y (ties to even, saturating at 448)."""
+    return int(lib().chai_oracle_e4m3_encode(float(np.float32(y))))
+
+
+def quantize_rows(x):
+    """x [..., d] fp32 or bf16 bits -> (codes uint8 [..., d], scales fp32 [...]): one scale per row."""
+    x = _c(x)
+    d = x.shape[-1]
+    n = int(np.prod(x.shape[:-1]))
+    codes = np.empty(x.shape, np.uint8)
+    scales = np.empty(x.shape[:-1], np.float32)
+    _check(lib().chai_oracle_quantize_rows(_p(x), n, d, _dtype_code(x), _p(codes), _p(scales)), "quantize_rows")
+    return codes, scales
+
+
+def dequantize_rows(codes, scales):
+    """codes uint8 [..., d], scales fp32 [...] -> f64 [..., d]."""
+    codes, scales = _c(codes, np.uint8), _c(scales, np.float32)
+    d = codes.shape[-1]
+    n = int(np.prod(codes.shape[:-1]))
+    assert scales.shape == codes.shape[:-1]
+    out = np.empty(codes.shape, np.float64)
+    _check(lib().chai_oracle_dequantize_rows(_p(codes), _p(scales), n, d, _p(out)), "dequantize_rows")
+    return out
+
+
+def clustered_decode_q8(q, k8, kscale, v8, vscale, head_to_cluster, rep_heads, T, scale, want_probs=False):
+    """Clustered decode over quantised FULL caches: q [B,H,d] (fp32 / bf16 bits); k8, v8 uint8 [B,H,T_cap,d];
+    kscale, vscale fp32 [B,H,T_cap].  Returns out [B,H,d] f64 (and probs [B,k,T])."""
+    q, k8, v8 = _c(q), _c(k8, np.uint8), _c(v8, np.uint8)
+    kscale, vscale = _c(kscale, np.float32), _c(vscale, np.float32)
+    B, H, d = q.shape
+    T_cap = k8.shape[2]
+    assert k8.shape == (B, H, T_cap, d) and v8.shape == (B, H, T_cap, d)
+    assert kscale.shape == (B, H, T_cap) and vscale.shape == (B, H, T_cap)
+    h2c = _c(head_to_cluster, np.int32)
+    rep = _c(rep_heads, np.int32)
+    k = rep.shape[1]
+    out = np.empty((B, H, d), np.float64)
+    probs = np.empty((B, k, T), np.float64) if want_probs else None
+    rc = lib().chai_oracle_clustered_decode_q8(_p(q), _p(k8), _p(kscale), _p(v8), _p(vscale), _p(h2c), _p(rep), B, H, k,
+                                               T, T_cap, d, _dtype_code(q), _f32(scale), _p(out), _p(probs))
+    _check(rc, "clustered_decode_q8")
+    return (out, probs) if want_probs else out

@@ -602,4 +602,134 @@ def pin_append_writes_one_row():
     assert np.array_equal(kc, ek) and np.array_equal(v, ev)
 
 
+# ----------------------------------------------------------------------------------------------
+# quantised caches: 8-bit floating point codes, per-row scales, attention over dequantised tensors
+# ----------------------------------------------------------------------------------------------
+def _finite_e4m3():
+    """(code, value) of every finite code, from the field layout written out here (not from the oracle)."""
+    out = []
+    for code in range(256):
+        sgn, e, m = code >> 7, (code >> 3) & 15, code & 7
+        if e == 15 and m == 7:
+            continue
+        mag = (m / 8.0) * 2.0 ** -6 if e == 0 else (1 + m / 8.0) * 2.0 ** (e - 7)
+        out.append((code, -mag if sgn else mag))
+    return out
+
+
+def pin_e4m3_codes_match_the_format():
+    import torch
+    g = _golden("e4m3_worked.json")
+    for c in g["codes"]:
+        assert O.e4m3_decode(c["code"]) == c["value"], c
+    for c in g["nan_codes"]:
+        assert math.isnan(O.e4m3_decode(c))
+    vals = [O.e4m3_decode(c) for c in range(0x7f)]
+    assert all(b > a for a, b in zip(vals, vals[1:])) and vals[0] == 0.0          # positive codes ascend
+    assert all(O.e4m3_decode(c | 0x80) == -O.e4m3_decode(c) for c in range(0x7f))
+    # a library's decoder of the same format, all 256 codes
+    lib = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+    mine = np.array([O.e4m3_decode(c) for c in range(256)])
+    assert np.array_equal(np.isnan(lib), np.isnan(mine)) and np.array_equal(lib[~np.isnan(lib)], mine[~np.isnan(mine)])
+    for code, value in _finite_e4m3():
+        assert mine[code] == value
+
+
+def pin_e4m3_encode_is_nearest_even():
+    import torch
+    g = _golden("e4m3_worked.json")
+    for c in g["encode"]:
+        assert O.e4m3_encode(c["y"]) == c["code"], c
+    table = _finite_e4m3()
+    codes = np.array([c for c, _ in table])
+    vals = np.array([v for _, v in table])
+    rng = np.random.default_rng(5150)
+    ys = np.concatenate([rng.standard_normal(3000) * 100, rng.standard_normal(3000), rng.standard_normal(3000) * 0.01,
+                         rng.uniform(-448, 448, 3000), [448.0, -448.0, 0.0, 2.0 ** -9, 2.0 ** -10]]).astype(np.float32)
+    ys = np.clip(ys, -448, 448)
+    # brute force: the finite value at the smallest distance; on a tie the code with an even mantissa
+    for y in ys[:4000]:
+        dist = np.abs(vals - np.float64(y))
+        best = np.flatnonzero(dist == dist.min())
+        want = {int(codes[i]) for i in best}
+        if len(want) > 1 and not (want == {0, 0x80}):
+            want = {c for c in want if c % 2 == 0}
+        got = O.e4m3_encode(y)
+        assert got in want or (y == 0 and got in (0, 0x80)), (float(y), got, want)
+    # a library's conversion of the same format
+    lib = torch.from_numpy(ys).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    mine = np.array([O.e4m3_encode(y) for y in ys], np.uint8)
+    assert np.array_equal(lib, mine)
+    # decode(encode(v)) returns every representable value
+    for code, value in table:
+        assert O.e4m3_decode(O.e4m3_encode(value)) == value
+
+
+def pin_quantized_rows():
+    g = _golden("e4m3_worked.json")
+    for row in g["rows"]:
+        codes, scale = O.quantize_rows(np.asarray(row["x"], np.float32)[None])
+        assert codes[0].tolist() == row["codes"], row
+        assert scale[0] == np.float32(row["scale"]), (row, scale)
+    rng = np.random.default_rng(5151)
+    for dtype in (W.F32, W.BF16):
+        x = W.normal(rng, (7, 33, 128), dtype, sigma=3.0)
+        xf = W.as_f64(x)
+        codes, scales = O.quantize_rows(x)
+        amax = np.abs(xf).max(-1)
+        assert np.array_equal(scales, (amax.astype(np.float32) / np.float32(448)).astype(np.float32))
+        deq = O.dequantize_rows(codes, scales)
+        # the element with the largest magnitude maps to +-448; nothing is off by more than half a spacing:
+        # 2^-4 relative for normal codes, half of the smallest step (2^-10 of the scale) below that
+        assert np.all(np.abs(np.vectorize(O.e4m3_decode)(codes)).max(-1) == 448.0)
+        bound = np.maximum(np.abs(xf) * 2.0 ** -4, scales[..., None].astype(np.float64) * 2.0 ** -10) * (1 + 1e-5)
+        assert np.all(np.abs(deq - xf) <= bound)
+        # scaling a row by a power of two leaves the codes alone and scales the scale
+        x4 = W.store(W.as_f64(x).astype(np.float32) * 4.0, dtype)
+        c4, s4 = O.quantize_rows(x4)
+        assert np.array_equal(c4, codes) and np.array_equal(s4, scales * np.float32(4))
+    # dequantisation is decode(code) * scale, against the library decoder
+    import torch
+    lib = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy() * scales[..., None].astype(np.float64)
+    assert np.array_equal(lib, deq)
+
+
+def pin_quantized_attention_matches_library():
+    import torch
+    rng = np.random.default_rng(5152)
+    B, H, kk, T, T_cap, d = 2, 6, 3, 37, 40, 16
+    scale = 0.25
+    for dtype in (W.F32, W.BF16):
+        q = W.normal(rng, (B, H, d), dtype)
+        kf = W.normal(rng, (B, H, T_cap, d), dtype)
+        vf = W.normal(rng, (B, H, T_cap, d), dtype, sigma=2.0)
+        h2c, rep = W.random_membership(rng, B, H, kk)
+        k8, ks = O.quantize_rows(kf)
+        v8, vs = O.quantize_rows(vf)
+        out, probs = O.clustered_decode_q8(q, k8, ks, v8, vs, h2c, rep, T, scale, want_probs=True)
+        # library: decode the codes with torch, scale per row, then softmax + contraction in numpy fp64
+        kd = torch.from_numpy(k8.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy() * ks[..., None].astype(np.float64)
+        vd = torch.from_numpy(v8.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy() * vs[..., None].astype(np.float64)
+        q64 = W.as_f64(q)
+        sc = np.float64(np.float32(scale))
+        for b in range(B):
+            for j in range(kk):
+                r = rep[b, j]
+                p = scipy.special.softmax(sc * kd[b, r, :T] @ q64[b, r])
+                assert np.abs(p - probs[b, j]).max() < 1e-13
+            for h in range(H):
+                p = scipy.special.softmax(sc * kd[b, rep[b, h2c[b, h]], :T] @ q64[b, rep[b, h2c[b, h]]])
+                assert np.abs(p @ vd[b, h, :T] - out[b, h]).max() < 1e-12
+        # the quantised result stays near the unquantised one (error of a few percent of the row scale at most)
+        plain = O.clustered_decode(q, kf, vf, h2c, rep, T, scale)
+        assert np.abs(out - plain).max() < 0.15 * np.abs(plain).max()
+        # scales that are all 1 and codes that are exact: identical to plain attention on the decoded values
+        ones = np.ones_like(ks)
+        kx = torch.from_numpy(k8.copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+        vx = torch.from_numpy(v8.copy()).view(torch.float8_e4m3fn).to(torch.float32).numpy()
+        a = O.clustered_decode_q8(q if dtype == W.F32 else W.as_f64(q).astype(np.float32), k8, ones, v8, ones, h2c, rep, T, scale)
+        bb = O.clustered_decode(W.as_f64(q).astype(np.float32), kx, vx, h2c, rep, T, scale)
+        assert np.abs(a - bb).max() < 1e-12 * max(1.0, np.abs(bb).max())
+
+
 ALL_PINS = [v for n, v in sorted(globals().items()) if n.startswith("pin_") and callable(v)]

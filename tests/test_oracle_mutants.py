@@ -101,6 +101,27 @@ MUTANTS = [
      ["pin_compaction_is_a_gather"]),
     ("append_all_keys_from_head_0", "(const char *)k_new + ((size_t)b * H + r) * row, row);", "(const char *)k_new + ((size_t)b * H + 0) * row, row);", 0,
      ["pin_append_writes_one_row"]),
+    ("e4m3_decode_bias_8", "else mag = ldexp(1.0 + (double)m / 8.0, e - 7);", "else mag = ldexp(1.0 + (double)m / 8.0, e - 8);", 0,
+     ["pin_e4m3_codes_match_the_format"]),
+    ("e4m3_decode_subnormals_as_normals", "if (e == 0) mag = ldexp((double)m / 8.0, 1 - 7);",
+     "if (e == 0) mag = ldexp(1.0 + (double)m / 8.0, 0 - 7);", 0, ["pin_e4m3_codes_match_the_format"]),
+    ("e4m3_encode_truncates", "double r = nearbyint(a / step);", "double r = floor(a / step);", 0,
+     ["pin_e4m3_encode_is_nearest_even"]),
+    ("e4m3_encode_ties_away_from_zero", "double r = nearbyint(a / step);", "double r = round(a / step);", 0,
+     ["pin_e4m3_encode_is_nearest_even"]),
+    ("e4m3_encode_no_subnormal_spacing", "if (e < -6) e = -6;", "if (e < -9) e = -9;", 0,
+     ["pin_e4m3_encode_is_nearest_even", "pin_quantized_rows"]),
+    ("e4m3_encode_does_not_saturate", "if (a >= 448.0) return sign | 0x7e;", "if (a >= 448.0) return sign | 0x7f;", 0,
+     ["pin_e4m3_encode_is_nearest_even", "pin_quantized_rows"]),
+    ("quantize_scale_to_240", "float scale = amax / 448.0f;", "float scale = amax / 240.0f;", 0, ["pin_quantized_rows"]),
+    ("quantize_amax_signed", "float v = fabsf((float)load_elem(x, r * d + i, dtype));", "float v = (float)load_elem(x, r * d + i, dtype);", 0,
+     ["pin_quantized_rows"]),
+    ("q8_key_scale_of_first_row", "* (double)kscale[row0 + t];", "* (double)kscale[row0];", 0,
+     ["pin_quantized_attention_matches_library"]),
+    ("q8_value_scale_dropped", "* (double)vscale[row0 + t];", ";", 0, ["pin_quantized_attention_matches_library"]),
+    ("q8_values_of_representative", "int64_t row0 = ((int64_t)b * H + h) * (int64_t)T_cap;",
+     "int64_t row0 = ((int64_t)b * H + rep_heads[(int64_t)b * k + c]) * (int64_t)T_cap;", 0,
+     ["pin_quantized_attention_matches_library"]),
     ("append_row_off_by_one", "* T_cap + pos) * row,", "* T_cap + pos - 1) * row,", 0, ["pin_append_writes_one_row"]),
 ]
 # a mutant made of several edits: the feature block computed without the causal mask
