@@ -32,7 +32,7 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--context", type=int, default=0, help="override the number of cached tokens (cfg4: 640 or 2048)")
-    ap.add_argument("--mode", default="decode", choices=["decode", "prefill", "shared-v", "project", "e2e"],
+    ap.add_argument("--mode", default="decode", choices=["decode", "prefill", "shared-v", "project", "e2e", "q8"],
                     help="decode (default, the headline metric), the clustered prefill attention, the decode "
                          "ablation that prunes values as well, or the query/key projections of the representatives")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -689,6 +689,90 @@ def decode_bench(cfg, args, torch, C, W, steps, warmup, want_cpu, want_dense=Tru
     return result
 
 
+def q8_bench(cfg, args, torch, C, W, steps, warmup, want_parity=True):
+    """Decode step over QUANTISED caches (8-bit floating point codes, one fp32 scale per cached row) of the same
+    configuration: the caches are built as for the bf16 path, quantised by the library, and attended to through
+    chai_decode_attention_q8.  Algorithmic bytes are the method's own for this storage: 132 bytes per cached row."""
+    import numpy as np
+    B, H, d, T = cfg.B, cfg.H, cfg.d, cfg.T
+    layers, _ = build_layers(cfg, W, C, torch, keep_full_k=want_parity)
+    q8 = []
+    for L in layers:
+        k8, ks = C.chai_quantize_rows(L.kc)
+        v8, vs = C.chai_quantize_rows(L.v)
+        q8.append((k8, ks, v8, vs))
+        L.kc = None
+        if not want_parity:
+            L.v = None
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    ws = torch.empty((C.chai_decode_q8_workspace_bytes(B, H, max(cfg.ks), T),), dtype=torch.uint8, device="cuda")
+
+    def step():
+        for L, (k8, ks, v8, vs) in zip(layers, q8):
+            C.chai_decode_attention_q8(L.q, k8, ks, v8, vs, L.h2c, L.rep, T, cfg.scale, L.out, ws)
+
+    ms, wall_ms = timed_steps(step, steps, warmup, torch)
+    row_bytes = d + 4
+    alg = sum(B * (L.k + H) * T * row_bytes + B * L.k * d * cfg.elem_bytes + 2 * B * H * 4 + B * H * d * 4 for L in layers)
+    hev = HipEvents()
+    recs = []
+    for _ in range(max(min(steps, 10), 2)):
+        for L, (k8, ks, v8, vs) in zip(layers, q8):
+            e = [hev.create() for _ in range(4)]
+            C.chai_decode_attention_q8_timed(L.q, k8, ks, v8, vs, L.h2c, L.rep, T, cfg.scale, L.out, ws,
+                                             score_events=(e[0], e[1]), value_events=(e[2], e[3]))
+            recs.append(e)
+    torch.cuda.synchronize()
+    s_ms = sum(hev.elapsed_ms(e[0], e[1]) for e in recs) / len(recs)
+    v_ms = sum(hev.elapsed_ms(e[2], e[3]) for e in recs) / len(recs)
+    hev.close()
+    v_bytes = B * H * T * row_bytes + B * H * d * 4
+    ach = v_bytes / (v_ms * 1e-3) / 1e9
+    rec = {"storage": "E4M3 codes + one fp32 scale per cached row (132 bytes per row instead of 256)",
+           "workload": f"{cfg.name}: {cfg.L} layers x {H} heads x d{d}, batch {B}, context {T}",
+           "tokens_per_s": B / (ms * 1e-3), "ms_per_step": ms, "algorithmic_bytes_per_step": alg,
+           "algorithmic_GBps": alg / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+           "roofline": {"bound": "hbm", "kernel": "value_kernel (8-bit rows)", "achieved": ach, "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": v_bytes,
+                        "avg_launch_ms": v_ms},
+           "score_kernel_ms": s_ms, "host_wall_ms_per_step": wall_ms}
+    if want_parity:
+        from oracle import chai_oracle as O
+        step()
+        torch.cuda.synchronize()
+        g = np.random.default_rng(cfg.seed + 8)
+        worst, codes_equal = 0.0, True
+        for li in sorted(set([0, len(layers) - 1])):
+            L, (k8, ks, v8, vs) = layers[li], q8[li]
+            h2c, rep = L.h2c.cpu().numpy(), L.rep.cpu().numpy()
+            for _ in range(4):
+                b, h = int(g.integers(B)), int(g.integers(H))
+                c = int(h2c[b, h])
+                r = int(rep[b, c])
+                # the oracle quantises the representative's FULL-cache key stream and this head's value stream itself
+                kq, ksq = O.quantize_rows(W.torch_to_host_bits(L.kfull[b, r, :T]))
+                vq, vsq = O.quantize_rows(W.torch_to_host_bits(L.v[b, h, :T]))
+                codes_equal = (codes_equal and np.array_equal(kq, k8[b, c, :T].cpu().numpy())
+                               and np.array_equal(ksq, ks[b, c, :T].cpu().numpy())
+                               and np.array_equal(vq, v8[b, h, :T].cpu().numpy())
+                               and np.array_equal(vsq, vs[b, h, :T].cpu().numpy()))
+                qr = W.torch_to_host_bits(L.q[b, r])
+                ref = O.clustered_decode_q8(np.stack([qr, qr * 0])[None], np.stack([kq, kq * 0])[None],
+                                            np.stack([ksq, ksq * 0])[None], np.stack([vq * 0, vq])[None],
+                                            np.stack([vsq * 0, vsq])[None], np.zeros((1, 2), np.int32),
+                                            np.zeros((1, 1), np.int32), T, cfg.scale)[0, 1]
+                got = L.out[b, h].cpu().numpy().astype(np.float64)
+                worst = max(worst, float(np.abs(got - ref).max() / np.abs(ref).max()))
+        rec["parity"] = {"worst_normwise_err_vs_oracle_on_same_codes": worst, "codes_and_scales_equal_oracle": codes_equal,
+                         "sampled_heads": 8}
+        if worst > 2e-5 or not codes_equal:
+            raise RuntimeError(f"quantised decode parity failed: {rec['parity']}")
+    del layers, q8, ws
+    torch.cuda.empty_cache()
+    return rec
+
+
 def e2e_bench(cfg, args, torch, C, W, steps_timed=2):
     """The end-to-end flow of the OPT-66B-shaped configuration, all layers at full size: caches hold a prompt of
     cfg.prompt tokens -> score features of the first five positions -> k-means -> K-cache compaction (timed: the
@@ -874,6 +958,14 @@ def main():
     if args.mode == "project":
         project_main(args, cfg, torch, C, W)
         return
+    if args.mode == "q8":
+        r = q8_bench(cfg, args, torch, C, W, args.steps, args.warmup, want_parity=not args.no_cpu_baseline)
+        r.update({"metric": "clustered decode-attn tokens/s over 8-bit quantised K,V caches", "value": r["tokens_per_s"],
+                  "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "higher_is_better": True,
+                  "scaling": "weak", "vs_baseline": None, "dtype": "e4m3 codes, f32 accumulate", "data": "synthetic",
+                  "config": {"workload": r["workload"]}})
+        print(json.dumps(r))
+        return
     if args.mode == "e2e":
         print(json.dumps({"metric": "end-to-end clustered decode with cache growth", "config": {"workload": cfg.name},
                           "e2e": e2e_bench(W.CONFIGS["cfg4"], args, torch, C, W)}))
@@ -900,6 +992,7 @@ def main():
         others["cfg4"]["fixed_context_640"] = brief(r640)
         others["cfg4"]["e2e"] = e2e_bench(c4, args, torch, C, W)
         result["configs"] = others
+        result["quantised_kv"] = q8_bench(cfg, args, torch, C, W, max(min(args.steps, 10), 2), 2)
 
     print(json.dumps(result))
 

@@ -346,6 +346,53 @@ int chai_append_kv_shared_v(const void *k_new, const void *v_new, const int32_t 
                             int dtype, void *stream);
 
 /*
+ * Quantised K,V caches (Section 2, related work: quantising the K,V cache is
+ * orthogonal to clustering heads and composes with it; the paper fixes no
+ * format).  Format used here: elements are 8-bit floating point E4M3 of the
+ * OCP 8-bit floating point specification (1 sign, 4 exponent bits with bias
+ * 7, 3 mantissa bits, subnormals, no infinities, largest finite value 448),
+ * with ONE fp32 scale per cached row (one token of one key or value stream):
+ *     scale = max_i |x_i| / 448,   code_i = nearest E4M3 (ties to even) of
+ *     x_i * (448 / max_i |x_i|),   all three operations in fp32;
+ * an all-zero row has scale 0 and codes 0.  The dequantised element is
+ * decode(code_i) * scale, and attention over quantised caches is attention
+ * over the dequantised caches.  A cache stream is then 132 bytes per token
+ * instead of 256.
+ *
+ * chai_quantize_rows: n_rows rows of d = 128 elements (dtype fp32 or bf16,
+ *   dense, 16-byte aligned) -> codes [n_rows,128] uint8 and scales [n_rows].
+ *   A whole cache [B,S,T_cap,128] is n_rows = B*S*T_cap rows.
+ * chai_append_kv_q8: cache growth by one token, quantising on the way in:
+ *     k8[b][j][pos], kscale[b][j][pos] <- quantised k_new[b][rep_heads[b][j]]
+ *     v8[b][h][pos], vscale[b][h][pos] <- quantised v_new[b][h]
+ *   k_new, v_new [B,H,d] in `dtype`; k8 [B,k,Tc_cap,d], kscale [B,k,Tc_cap];
+ *   v8 [B,H,T_cap,d], vscale [B,H,T_cap].
+ * chai_decode_attention_q8: chai_decode_attention over such caches.  q stays
+ *   unquantised ([B,H,d] in q_dtype); out, probs_out, maps, limits and errors
+ *   as chai_decode_attention; workspace of chai_decode_q8_workspace_bytes
+ *   bytes (monotone in T).  The _timed form also takes two pairs of HIP
+ *   events (any of them NULL) that the runtime stamps with the begin and the
+ *   end of the score kernel and of the value kernel.
+ */
+int chai_quantize_rows(const void *x, int dtype, long long n_rows, int d, uint8_t *codes, float *scales,
+                       void *stream);
+int chai_append_kv_q8(const void *k_new, const void *v_new, const int32_t *rep_heads, uint8_t *k8,
+                      float *kscale, uint8_t *v8, float *vscale, int B, int H, int k, int pos, int Tc_cap,
+                      int T_cap, int d, int dtype, void *stream);
+size_t chai_decode_q8_workspace_bytes(int B, int H, int k, int T, int d);
+int chai_decode_attention_q8(const void *q, const uint8_t *k8, const float *kscale, const uint8_t *v8,
+                             const float *vscale, const int32_t *head_to_cluster, const int32_t *rep_heads,
+                             int B, int H, int k, int T, int Tc_cap, int T_cap, int d, int q_dtype,
+                             float scale, float *out, float *probs_out, void *workspace,
+                             size_t workspace_bytes, void *stream);
+int chai_decode_attention_q8_timed(const void *q, const uint8_t *k8, const float *kscale, const uint8_t *v8,
+                                   const float *vscale, const int32_t *head_to_cluster,
+                                   const int32_t *rep_heads, int B, int H, int k, int T, int Tc_cap, int T_cap,
+                                   int d, int q_dtype, float scale, float *out, float *probs_out,
+                                   void *workspace, size_t workspace_bytes, void *stream, void *score_start,
+                                   void *score_stop, void *value_start, void *value_stop);
+
+/*
  * Dense multi-head decode attention, the definition of Section 2
  * (A_h = softmax(q_h K_h^T / sqrt(d)), y = A_0 V_0 (+) A_1 V_1 ...): the
  * baseline clustered attention is compared against.  Runs the same kernels

@@ -26,7 +26,8 @@ EXPORTS = ["chai_version", "chai_status_string", "chai_score_features", "chai_as
            "chai_cluster_error", "chai_pick_cluster_count", "chai_closest_representatives",
            "chai_decode_attention_shared_v", "chai_append_kv_shared_v",
            "chai_compact_kcache", "chai_append_kv", "chai_decode_workspace_bytes", "chai_decode_attention", "chai_decode_step",
-           "chai_decode_attention_static",
+           "chai_decode_attention_static", "chai_quantize_rows", "chai_append_kv_q8", "chai_decode_q8_workspace_bytes",
+           "chai_decode_attention_q8", "chai_decode_attention_q8_timed",
            "chai_decode_scores", "chai_decode_values", "chai_decode_scores_timed", "chai_decode_values_timed",
            "chai_dense_decode_attention", "chai_prefill_workspace_bytes", "chai_prefill_attention",
            "chai_prefill_attention_timed", "chai_dense_prefill_attention", "chai_project_qk", "chai_project_qk_timed", "chai_stream_read_probe", "chai_mfma_rate_probe"]
@@ -58,6 +59,12 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_decode_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
     L.chai_decode_attention.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, vp, sz, vp]
     L.chai_decode_attention_static.argtypes = [vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, vp]
+    L.chai_quantize_rows.argtypes = [vp, ci, ctypes.c_longlong, ci, vp, vp, vp]
+    L.chai_append_kv_q8.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, vp]
+    L.chai_decode_q8_workspace_bytes.restype = sz
+    L.chai_decode_q8_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    L.chai_decode_attention_q8.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, vp, sz, vp]
+    L.chai_decode_attention_q8_timed.argtypes = L.chai_decode_attention_q8.argtypes + [vp, vp, vp, vp]
     L.chai_decode_step.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     L.chai_dense_decode_attention.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     L.chai_decode_scores.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, sz, vp]
@@ -77,7 +84,8 @@ def _load(path: str = LIB_PATH) -> ctypes.CDLL:
     L.chai_prefill_attention_timed.argtypes = L.chai_prefill_attention.argtypes + [vp, vp]
     L.chai_dense_prefill_attention.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, ci, ci, cf, vp, vp, sz, vp]
     for fn in EXPORTS:
-        if fn not in ("chai_status_string", "chai_decode_workspace_bytes", "chai_prefill_workspace_bytes"):
+        if fn not in ("chai_status_string", "chai_decode_workspace_bytes", "chai_prefill_workspace_bytes",
+                      "chai_decode_q8_workspace_bytes"):
             getattr(L, fn).restype = ci
     return L
 
@@ -294,6 +302,63 @@ def chai_decode_attention_static(q, k_compact, v_cache, head_to_cluster, rep_hea
            _lib.chai_decode_attention_static(_ptr(q), _ptr(k_compact), _ptr(v_cache), _ptr(head_to_cluster),
                                              _ptr(rep_heads), B, H, k, T, Tc_cap, T_cap, d, dtype_code(q), scale,
                                              _ptr(out), _ptr(probs_out), _stream(stream)))
+    return out
+
+
+def chai_quantize_rows(x, codes=None, scales=None, stream=None):
+    """x [..., 128] fp32 or bf16 -> (codes uint8 [..., 128], scales fp32 [...]): E4M3 codes, one scale per row."""
+    d = x.shape[-1]
+    n_rows = x.numel() // d
+    if codes is None:
+        codes = torch.empty(x.shape, dtype=torch.uint8, device=x.device)
+    if scales is None:
+        scales = torch.empty(x.shape[:-1], dtype=torch.float32, device=x.device)
+    _check("chai_quantize_rows",
+           _lib.chai_quantize_rows(_ptr(x), dtype_code(x), n_rows, d, _ptr(codes), _ptr(scales), _stream(stream)))
+    return codes, scales
+
+
+def chai_append_kv_q8(k_new, v_new, rep_heads, k8, kscale, v8, vscale, pos: int, stream=None):
+    """Quantise the new token's rows into the 8-bit caches: k8 [B,k,Tc_cap,d] + kscale [B,k,Tc_cap], v8 [B,H,T_cap,d] +
+    vscale [B,H,T_cap]."""
+    B, H, d = k_new.shape
+    k, Tc_cap = k8.shape[1], k8.shape[2]
+    T_cap = v8.shape[2]
+    _check("chai_append_kv_q8",
+           _lib.chai_append_kv_q8(_ptr(k_new), _ptr(v_new), _ptr(rep_heads), _ptr(k8), _ptr(kscale), _ptr(v8), _ptr(vscale),
+                                  B, H, k, pos, Tc_cap, T_cap, d, dtype_code(k_new), _stream(stream)))
+
+
+def chai_decode_q8_workspace_bytes(B: int, H: int, k: int, T: int, d: int = 128) -> int:
+    return int(_lib.chai_decode_q8_workspace_bytes(B, H, k, T, d))
+
+
+def chai_decode_attention_q8_timed(q, k8, kscale, v8, vscale, head_to_cluster, rep_heads, T: int, scale: float, out,
+                                   workspace, probs_out=None, stream=None, score_events=(None, None),
+                                   value_events=(None, None)):
+    """chai_decode_attention over caches of E4M3 codes with per-row scales; events: raw hipEvent_t handles or None."""
+    B, H, d = q.shape
+    k, Tc_cap = k8.shape[1], k8.shape[2]
+    T_cap = v8.shape[2]
+    _check("chai_decode_attention_q8",
+           _lib.chai_decode_attention_q8_timed(_ptr(q), _ptr(k8), _ptr(kscale), _ptr(v8), _ptr(vscale),
+                                               _ptr(head_to_cluster), _ptr(rep_heads), B, H, k, T, Tc_cap, T_cap, d,
+                                               dtype_code(q), scale, _ptr(out), _ptr(probs_out), _ptr(workspace),
+                                               workspace.numel() * workspace.element_size(), _stream(stream),
+                                               score_events[0], score_events[1], value_events[0], value_events[1]))
+    return out
+
+
+def chai_decode_attention_q8(q, k8, kscale, v8, vscale, head_to_cluster, rep_heads, T: int, scale: float, out, workspace,
+                             probs_out=None, stream=None):
+    B, H, d = q.shape
+    k, Tc_cap = k8.shape[1], k8.shape[2]
+    T_cap = v8.shape[2]
+    _check("chai_decode_attention_q8",
+           _lib.chai_decode_attention_q8(_ptr(q), _ptr(k8), _ptr(kscale), _ptr(v8), _ptr(vscale), _ptr(head_to_cluster),
+                                         _ptr(rep_heads), B, H, k, T, Tc_cap, T_cap, d, dtype_code(q), scale, _ptr(out),
+                                         _ptr(probs_out), _ptr(workspace), workspace.numel() * workspace.element_size(),
+                                         _stream(stream)))
     return out
 
 

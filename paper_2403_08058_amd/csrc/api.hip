@@ -337,6 +337,76 @@ int chai_decode_step(const void *q, const void *k_new, const void *v_new, void *
                                     workspace, plan, false, KernelEvents(), s, nullptr, v_new));
 }
 
+int chai_quantize_rows(const void *x, int dtype, long long n_rows, int d, uint8_t *codes, float *scales, void *stream)
+{
+    if (!x || !codes || !scales) return CHAI_ERR_NULL;
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (n_rows < 0 || d < 1) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || n_rows > (1LL << 34)) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(x) || !aligned16(codes)) return CHAI_ERR_ALIGN;
+    if (n_rows == 0) return CHAI_OK;
+    return hip_status(launch_quantize_rows(x, dtype, n_rows, codes, scales, static_cast<hipStream_t>(stream)));
+}
+
+int chai_append_kv_q8(const void *k_new, const void *v_new, const int32_t *rep_heads, uint8_t *k8, float *kscale,
+                      uint8_t *v8, float *vscale, int B, int H, int k, int pos, int Tc_cap, int T_cap, int d, int dtype,
+                      void *stream)
+{
+    if (!k_new || !v_new || !rep_heads || !k8 || !kscale || !v8 || !vscale) return CHAI_ERR_NULL;
+    if (bad_dtype(dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || k < 1 || k > H || pos < 0 || pos >= T_cap || pos >= Tc_cap || d < 1) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || B > kMaxGridYZ) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(k_new) || !aligned16(v_new) || !aligned16(k8) || !aligned16(v8)) return CHAI_ERR_ALIGN;
+    if (B == 0) return CHAI_OK;
+    return hip_status(launch_append_kv_q8(k_new, v_new, rep_heads, k8, kscale, v8, vscale, B, H, k, pos, Tc_cap, T_cap,
+                                          dtype, static_cast<hipStream_t>(stream)));
+}
+
+size_t chai_decode_q8_workspace_bytes(int B, int H, int k, int T, int d)
+{
+    if (B < 0 || H < 1 || k < 1 || k > H || T < 1 || d != kHeadDim) return 0;
+    if (B == 0) return 256;
+    return make_decode_plan(B, H, k, T, false).bytes;
+}
+
+int chai_decode_attention_q8_timed(const void *q, const uint8_t *k8, const float *kscale, const uint8_t *v8,
+                                   const float *vscale, const int32_t *head_to_cluster, const int32_t *rep_heads, int B,
+                                   int H, int k, int T, int Tc_cap, int T_cap, int d, int q_dtype, float scale,
+                                   float *out, float *probs_out, void *workspace, size_t workspace_bytes, void *stream,
+                                   void *score_start, void *score_stop, void *value_start, void *value_stop)
+{
+    if (!q || !k8 || !kscale || !v8 || !vscale || !head_to_cluster || !rep_heads || !out) return CHAI_ERR_NULL;
+    if (bad_dtype(q_dtype)) return CHAI_ERR_DTYPE;
+    if (B < 0 || H < 1 || k < 1 || k > H || T < 1 || T > T_cap || T > Tc_cap || d < 1) return CHAI_ERR_SHAPE;
+    if (d != kHeadDim || B > kMaxGridYZ || H > kMaxGridYZ) return CHAI_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k8) || !aligned16(v8) || !aligned16(out)) return CHAI_ERR_ALIGN;
+    const DecodePlan plan = make_decode_plan(B, H, k, T, false);
+    if (B > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 || workspace_bytes < plan.bytes))
+        return CHAI_ERR_WORKSPACE;
+    if (B == 0) return CHAI_OK;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    KernelEvents es, evv;
+    es.start = static_cast<hipEvent_t>(score_start);
+    es.stop = static_cast<hipEvent_t>(score_stop);
+    evv.start = static_cast<hipEvent_t>(value_start);
+    evv.stop = static_cast<hipEvent_t>(value_stop);
+    const int st = hip_status(launch_scores_q8(q, q_dtype, k8, kscale, rep_heads, B, H, k, T, Tc_cap, scale, workspace,
+                                               plan, es, s));
+    if (st != CHAI_OK) return st;
+    return hip_status(launch_values_q8(v8, vscale, head_to_cluster, rep_heads, B, H, k, T, T_cap, out, probs_out, workspace,
+                                       plan, evv, s));
+}
+
+int chai_decode_attention_q8(const void *q, const uint8_t *k8, const float *kscale, const uint8_t *v8,
+                             const float *vscale, const int32_t *head_to_cluster, const int32_t *rep_heads, int B, int H,
+                             int k, int T, int Tc_cap, int T_cap, int d, int q_dtype, float scale, float *out,
+                             float *probs_out, void *workspace, size_t workspace_bytes, void *stream)
+{
+    return chai_decode_attention_q8_timed(q, k8, kscale, v8, vscale, head_to_cluster, rep_heads, B, H, k, T, Tc_cap, T_cap,
+                                          d, q_dtype, scale, out, probs_out, workspace, workspace_bytes, stream, nullptr,
+                                          nullptr, nullptr, nullptr);
+}
+
 int chai_append_kv_shared_v(const void *k_new, const void *v_new, const int32_t *rep_heads, void *k_compact,
                             void *v_compact, int B, int H, int k, int pos, int Tc_cap, int Tv_cap, int d, int dtype,
                             void *stream)

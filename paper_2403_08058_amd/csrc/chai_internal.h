@@ -26,7 +26,8 @@ struct DecodePlan {
     size_t off_scores, off_stats, off_partial, off_rows, bytes;   // off_rows: [B,H,128] fp32 staging rows
 };
 
-DecodePlan make_decode_plan(int B, int H, int k, int T);
+// column_split = false: never cut rows into column parts (caches whose rows are a single cache line)
+DecodePlan make_decode_plan(int B, int H, int k, int T, bool column_split = true);
 
 // Kernels that use more than 64 KB of dynamic LDS must be told so once on every device they run on.  `done` is the
 // caller's per-kernel table (zero-initialised, one flag per device ordinal); a repeated call costs one hipGetDevice.
@@ -84,6 +85,20 @@ int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
                   int dtype, float *out, float *probs_out, void *workspace, const DecodePlan &plan, bool identity,
                   const KernelEvents &ev, hipStream_t stream, const MemberRows *members = nullptr,
                   const void *v_new = nullptr);
+
+// The same two kernels over caches of 8-bit E4M3 codes with one fp32 scale per row; q stays fp32 or bf16 (q_dtype).
+// The plan must have been made with column_split = false.
+int launch_scores_q8(const void *q, int q_dtype, const void *k8, const float *kscale, const int32_t *rep, int B, int H,
+                     int k, int T, int Tc_cap, float scale, void *workspace, const DecodePlan &plan,
+                     const KernelEvents &ev, hipStream_t stream);
+int launch_values_q8(const void *v8, const float *vscale, const int32_t *h2c, const int32_t *rep, int B, int H, int k,
+                     int T, int T_cap, float *out, float *probs_out, void *workspace, const DecodePlan &plan,
+                     const KernelEvents &ev, hipStream_t stream);
+// rows of 128 elements (fp32 / bf16) -> E4M3 codes + one fp32 scale per row
+int launch_quantize_rows(const void *x, int dtype, long long n_rows, uint8_t *codes, float *scales, hipStream_t stream);
+int launch_append_kv_q8(const void *k_new, const void *v_new, const int32_t *rep, uint8_t *k8, float *kscale, uint8_t *v8,
+                        float *vscale, int B, int H, int k, int pos, int Tc_cap, int T_cap, int dtype,
+                        hipStream_t stream);
 
 int launch_score_features(const void *q5, const void *k5, int B, int H, int n_tok, int dtype, int64_t qs,
                           int64_t ks, float scale, float *feat, hipStream_t stream);

@@ -1,8 +1,10 @@
 // Clustered-head decode attention for gfx950 (MI355X): the score kernel streams the compact K cache once per
 // cluster, the value kernel streams the full V cache once per head.  Both are HBM-bandwidth kernels: every
-// lane issues 16-byte non-temporal loads, 16 lanes (bf16) or 32 lanes (fp32) cover one 128-element row, a
-// wave64 load instruction covers 1 KiB of consecutive rows, a wave keeps 8 KiB (one batch) or more in flight
-// and the four waves of a workgroup walk neighbouring batches of one contiguous region.
+// lane issues 16-byte non-temporal loads, 8 lanes (8-bit codes), 16 lanes (bf16) or 32 lanes (fp32) cover one
+// 128-element row, a wave64 load instruction covers 1 KiB of consecutive rows, a wave keeps 8 KiB (one batch) or
+// more in flight and the waves of a workgroup walk neighbouring batches of one contiguous region.  Caches of
+// 8-bit floating point codes (E4M3, one fp32 scale per row) go through the same kernels: the codes are widened
+// by the hardware conversion, the row's scale is folded into the row's score (keys) or probability (values).
 //
 // Method: attention definition of Section 2; one score computation per cluster with the representative's
 // query and keys, shared by the member heads, each applying it to its own values (Sections 3.4-3.5, Fig. 3).
@@ -18,25 +20,34 @@ constexpr int kUnroll = 8;        // 16-byte loads per lane in one batch
 constexpr int kScoreWaves = 4;    // waves per workgroup of the score kernel ...
 constexpr int kScoreBatches = 2;  // ... each with this many batches in flight
 
-template <bool BF16>
+// storage types of the caches inside this file: CHAI_F32, CHAI_BF16, and 8-bit E4M3 codes with per-row scales
+constexpr int DT_F32 = CHAI_F32, DT_BF16 = CHAI_BF16, DT_E4M3 = 2;
+template <int DT>
+struct Elem {
+    static constexpr int BYTES = DT == DT_F32 ? 4 : (DT == DT_BF16 ? 2 : 1);
+    static constexpr int EPL = 16 / BYTES;                 // elements per lane per load (16 bytes)
+};
+
+template <int DT>
 struct Tile {
-    static constexpr int EPL = BF16 ? 8 : 4;               // elements per lane per load (16 bytes)
-    static constexpr int LPR = kHeadDim / EPL;             // lanes per row: 16 (bf16) / 32 (fp32)
-    static constexpr int RPW = 64 / LPR;                   // rows per wave load: 4 / 2
-    static constexpr int BATCH = RPW * kUnroll;            // rows per wave batch: 32 / 16
-    static constexpr int ROW_BYTES = kHeadDim * (BF16 ? 2 : 4);
+    static constexpr int EPL = Elem<DT>::EPL;
+    static constexpr int LPR = kHeadDim / EPL;             // lanes per row: 32 (fp32) / 16 (bf16) / 8 (codes)
+    static constexpr int RPW = 64 / LPR;                   // rows per wave load: 2 / 4 / 8
+    static constexpr int BATCH = RPW * kUnroll;            // rows per wave batch: 16 / 32 / 64
+    static constexpr int ROW_BYTES = kHeadDim * Elem<DT>::BYTES;
 };
 
 // Value kernel: a workgroup may take only one of DS column parts of its head's rows (DS = 1: whole rows).
-template <bool BF16, int DS>
+template <int DT, int DS>
 struct VTile {
-    static constexpr int EPL = BF16 ? 8 : 4;
+    static constexpr int EPL = Elem<DT>::EPL;
     static constexpr int COLS = kHeadDim / DS;             // columns of this workgroup
     static constexpr int LPR = COLS / EPL;                 // lanes per (part of a) row
     static constexpr int RPW = 64 / LPR;                   // rows per wave load
     static constexpr int BATCH = RPW * kUnroll;            // rows per wave batch (at most 64)
-    static constexpr int ROW_BYTES = kHeadDim * (BF16 ? 2 : 4);
+    static constexpr int ROW_BYTES = kHeadDim * Elem<DT>::BYTES;
     static constexpr int PART_BYTES = ROW_BYTES / DS;
+    static_assert(BATCH <= 64, "one lane per row of a batch turns its score into a probability");
 };
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
@@ -48,6 +59,19 @@ __device__ __forceinline__ void unpack(const u32x4 &raw, float (&f)[8])
     f[2] = __uint_as_float(raw.y << 16); f[3] = __uint_as_float(raw.y & 0xffff0000u);
     f[4] = __uint_as_float(raw.z << 16); f[5] = __uint_as_float(raw.z & 0xffff0000u);
     f[6] = __uint_as_float(raw.w << 16); f[7] = __uint_as_float(raw.w & 0xffff0000u);
+}
+
+// sixteen E4M3 codes: the hardware conversion widens two bytes of a word at a time (exact)
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ void unpack(const u32x4 &raw, float (&f)[16])
+{
+    const unsigned int w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], false);
+        const f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[i], true);
+        f[4 * i + 0] = lo.x; f[4 * i + 1] = lo.y; f[4 * i + 2] = hi.x; f[4 * i + 3] = hi.y;
+    }
 }
 
 __device__ __forceinline__ void unpack(const u32x4 &raw, float (&f)[4])
@@ -72,14 +96,14 @@ __device__ __forceinline__ float dpp_add(float x)
 }
 
 // Sum over the lanes that share a row; every one of them ends up with the total.
-template <bool BF16>
+template <int DT>
 __device__ __forceinline__ float row_sum(float x)
 {
     x = dpp_add<0xB1>(x);    // quad_perm [1,0,3,2]: lane ^ 1
     x = dpp_add<0x4E>(x);    // quad_perm [2,3,0,1]: lane ^ 2
-    x = dpp_add<0x141>(x);   // row_half_mirror: other quad of the same 8 lanes
-    x = dpp_add<0x140>(x);   // row_mirror: other half of the same 16 lanes
-    if (!BF16) x += __shfl_xor(x, 16);   // fp32 rows span 32 lanes
+    x = dpp_add<0x141>(x);   // row_half_mirror: other quad of the same 8 lanes (rows of 8-bit codes end here)
+    if (DT != DT_E4M3) x = dpp_add<0x140>(x);   // row_mirror: other half of the same 16 lanes
+    if (DT == DT_F32) x += __shfl_xor(x, 16);   // fp32 rows span 32 lanes
     return x;
 }
 
@@ -114,16 +138,16 @@ __device__ __forceinline__ float wave_sum(float x)
 // DS = 2: two workgroups per head, each with half of the columns of every row (128-byte pieces, whole cache
 // lines): twice the workgroups without partial rows to add up afterwards -- for head counts that are too small
 // for one workgroup per head and would otherwise pay a combine launch.  grid = (n_cp, H * DS, B).
-template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND, int DS>
+template <int DT, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND, int DS>
 __device__ __forceinline__ void value_block(const char *__restrict__ v, const int32_t *__restrict__ h2c,
                                             const int32_t *__restrict__ rep, int H, int k, int T, int T_cap,
                                             int n_rec, int cp, int n_cp,
                                             const float *__restrict__ scores, const float2 *__restrict__ stats,
                                             float *__restrict__ partial, float *__restrict__ out,
                                             float *__restrict__ probs_out, const char *__restrict__ v_new,
-                                            int split, int hy, int b)
+                                            const float *__restrict__ vscale, int split, int hy, int b)
 {
-    using TL = VTile<BF16, DS>;
+    using TL = VTile<DT, DS>;
     __shared__ float p_lds[NW][TL::BATCH];
     __shared__ float acc_lds[NW][TL::COLS];
 
@@ -143,10 +167,13 @@ __device__ __forceinline__ void value_block(const char *__restrict__ v, const in
     const unsigned int lane_off = dpart * TL::PART_BYTES + cg * 16;
 
     // one batch: the 16-byte pieces of kUnroll * RPW consecutive rows, and (lanes < BATCH) one row's score
+    // (rows of 8-bit codes: also the row's scale)
     struct Batch {
         u32x4 v[kUnroll];
         float s;
+        float vs;
     };
+    const float *vsrow = DT == DT_E4M3 ? vscale + ((size_t)b * H + h) * T_cap + t0 : nullptr;
     Batch buf[NB];
 
     // Rows of batch `it` of this wave start at (it * NW + w) * BATCH within the chunk.  Every batch issues the
@@ -175,6 +202,7 @@ __device__ __forceinline__ void value_block(const char *__restrict__ v, const in
     auto request_s = [&](Batch &bt, int it) {
         const int tl = (it * NW + w) * TL::BATCH + lane;
         bt.s = srow[clamp_row(tl)];           // masked when it is consumed
+        if (DT == DT_E4M3) bt.vs = vsrow[clamp_row(tl)];
     };
 #pragma unroll
     for (int j = 0; j < NB; ++j) request_s(buf[j], j);
@@ -197,7 +225,8 @@ __device__ __forceinline__ void value_block(const char *__restrict__ v, const in
         const int tl = (it * NW + w) * TL::BATCH + lane;
         const float p = tl < n ? expf(bt.s - M) * inv : 0.f;          // rows past the end weigh nothing
         if (lane < TL::BATCH) {
-            p_lds[w][(lane % TL::RPW) * kUnroll + lane / TL::RPW] = p;
+            // a quantised row's scale rides on its probability: p * (scale * code) = (p * scale) * code
+            p_lds[w][(lane % TL::RPW) * kUnroll + lane / TL::RPW] = DT == DT_E4M3 ? p * bt.vs : p;
             if (WRITE_P) {
                 if (prow != nullptr && tl < n) prow[tl] = p;
             }
@@ -261,7 +290,7 @@ __device__ __forceinline__ void value_block(const char *__restrict__ v, const in
     }
 }
 
-template <bool BF16, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND, int DS>
+template <int DT, bool IDENT, int NW, int NB, bool WRITE_P, bool APPEND, int DS>
 __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__ v,
                                                         const int32_t *__restrict__ h2c,
                                                         const int32_t *__restrict__ rep, int H, int k, int T,
@@ -270,11 +299,12 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
                                                         const float2 *__restrict__ stats,
                                                         float *__restrict__ partial, float *__restrict__ out,
                                                         float *__restrict__ probs_out,
-                                                        const char *__restrict__ v_new)
+                                                        const char *__restrict__ v_new,
+                                                        const float *__restrict__ vscale)
 {
-    value_block<BF16, IDENT, NW, NB, WRITE_P, APPEND, DS>(v, h2c, rep, H, k, T, T_cap, n_rec, cp, n_cp, scores,
-                                                          stats, partial, out, probs_out, v_new, blockIdx.x,
-                                                          blockIdx.y, blockIdx.z);
+    value_block<DT, IDENT, NW, NB, WRITE_P, APPEND, DS>(v, h2c, rep, H, k, T, T_cap, n_rec, cp, n_cp, scores, stats,
+                                                        partial, out, probs_out, v_new, vscale, blockIdx.x, blockIdx.y,
+                                                        blockIdx.z);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -292,14 +322,16 @@ __global__ __launch_bounds__(NW * 64) void value_kernel(const char *__restrict__
 // the last chunk takes it from k_new [B,H,d] (row of the representative), scores it, and writes it to the cache,
 // so that growing the cache costs no launch of its own.
 // ---------------------------------------------------------------------------------------------------------
-template <bool BF16, bool IDENT, bool APPEND, int NW, int NB>
+template <int DT, bool IDENT, bool APPEND, int NW, int NB>
 __global__ __launch_bounds__(NW * 64) void score_kernel(const char *__restrict__ q, const char *__restrict__ kc,
                                                         const int32_t *__restrict__ rep, int H, int k, int T,
                                                         int Tc_cap, float scale, int cs, int n_cs,
                                                         float *__restrict__ scores, float2 *__restrict__ stats,
-                                                        const char *__restrict__ k_new)
+                                                        const char *__restrict__ k_new,
+                                                        const float *__restrict__ kscale, int q_dtype)
 {
-    using TL = Tile<BF16>;
+    using TL = Tile<DT>;
+    static_assert(!(APPEND && DT == DT_E4M3), "quantised caches grow through their own append kernel");
     const int chunk = blockIdx.x, j = blockIdx.y, b = blockIdx.z;
     const int tid = threadIdx.x;
     const int lane = tid & 63, w = tid >> 6;
@@ -314,21 +346,44 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const char *__restrict__
     const char *kbase = kc + (((size_t)b * k + j) * Tc_cap + t0) * TL::ROW_BYTES;
     const unsigned int lane_off = cg * 16;
     u32x4 buf[NB][kUnroll];
+    float ks_buf[NB];                        // rows of 8-bit codes: the scale of the row this lane will own
+    const float *ksrow = DT == DT_E4M3 ? kscale + ((size_t)b * k + j) * Tc_cap + t0 : nullptr;
     auto clamp_row = [&](int row) { return APPEND ? max(min(row, n - 1), 0) : min(row, n - 1); };
-    auto request = [&](u32x4 (&bt)[kUnroll], int it) {
+    auto request = [&](u32x4 (&bt)[kUnroll], float &ks, int it) {
         const int r0 = (it * NW + w) * TL::BATCH + rg;
 #pragma unroll
         for (int u = 0; u < kUnroll; ++u)
             bt[u] = stream16(kbase + ((unsigned int)clamp_row(r0 + u * TL::RPW) * TL::ROW_BYTES + lane_off));
+        if (DT == DT_E4M3) ks = ksrow[clamp_row(r0 + cg * TL::RPW)];
     };
 #pragma unroll
-    for (int i = 0; i < NB; ++i) request(buf[i], i);
+    for (int i = 0; i < NB; ++i) request(buf[i], ks_buf[i], i);
 
     int r = IDENT ? j : rep[(size_t)b * k + j];
     if (r < 0) return;                       // unused cluster slot (same decision for every wave of the chunk)
     r = min(r, H - 1);
     float qf[TL::EPL];
-    {
+    if (DT == DT_E4M3) {
+        // the query is not quantised: fp32 or bf16 (q_dtype), elements cg*16 .. cg*16+15 for this lane
+        const char *qrow = q + ((size_t)b * H + r) * (size_t)(kHeadDim * (q_dtype == CHAI_BF16 ? 2 : 4));
+        if (q_dtype == CHAI_BF16) {
+#pragma unroll
+            for (int part = 0; part < 2; ++part) {
+                float f8[8];
+                unpack(*reinterpret_cast<const u32x4 *>(qrow + cg * 32 + part * 16), f8);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) qf[(part * 8 + e) % TL::EPL] = f8[e];
+            }
+        } else {
+#pragma unroll
+            for (int part = 0; part < 4; ++part) {
+                float f4[4];
+                unpack(*reinterpret_cast<const u32x4 *>(qrow + cg * 64 + part * 16), f4);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) qf[(part * 4 + e) % TL::EPL] = f4[e];
+            }
+        }
+    } else {
         const u32x4 qraw = *reinterpret_cast<const u32x4 *>(q + ((size_t)b * H + r) * TL::ROW_BYTES + lane_off);
         unpack(qraw, qf);
     }
@@ -337,9 +392,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const char *__restrict__
     // The stored score is the ROUNDED product: the statistics below and the value kernel must both start from
     // that value (a multiply fused into the subtraction of the running maximum would use the unrounded one,
     // and with scores of magnitude 10^3 the difference reaches 1e-4 of a probability).
-    auto scaled = [&](float x) {
+    auto scaled = [&](float x, float row_scale) {
 #pragma clang fp contract(off)
-        return scale * x;
+        return DT == DT_E4M3 ? (scale * row_scale) * x : scale * x;
     };
     auto see = [&](float sv) {               // running softmax statistics of this lane
         const float m_new = fmaxf(m_run, sv);
@@ -359,13 +414,14 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const char *__restrict__
                 float dot = 0.f;
 #pragma unroll
                 for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
-                dot = row_sum<BF16>(dot);
+                dot = row_sum<DT>(dot);
                 mine = cg == u ? dot : mine;
             }
-            request(buf[i], it + NB);
+            const float ks = DT == DT_E4M3 ? ks_buf[i] : 1.f;
+            request(buf[i], ks_buf[i], it + NB);
             const int tl = (it * NW + w) * TL::BATCH + rg + cg * TL::RPW;
             if (cg < kUnroll && tl < n) {
-                const float sv = scaled(mine);
+                const float sv = scaled(mine, ks);
                 srow[tl] = sv;
                 see(sv);
             }
@@ -379,9 +435,9 @@ __global__ __launch_bounds__(NW * 64) void score_kernel(const char *__restrict__
             float dot = 0.f;
 #pragma unroll
             for (int e = 0; e < TL::EPL; ++e) dot = fmaf(qf[e], f[e], dot);
-            dot = row_sum<BF16>(dot);
+            dot = row_sum<DT>(dot);
             if (cg == 0) {
-                const float sv = scaled(dot);
+                const float sv = scaled(dot, 1.f);
                 srow[n] = sv;
                 see(sv);
             }
@@ -436,19 +492,22 @@ struct Workspace {
 
 // Launches carry the optional pair of events that the runtime stamps with the begin and the end of the kernel
 // itself (both NULL for an ordinary launch), for callers who profile.
-template <bool BF16, bool IDENT>
+template <int DT, bool IDENT>
 int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H, int k, int T, int Tc_cap,
                  float scale, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev, hipStream_t stream,
-                 const void *k_new)
+                 const void *k_new, const float *kscale = nullptr, int q_dtype = DT)
 {
     const dim3 grid(pl.n_cs, k, B), block(kScoreWaves * 64);
     const char *qc = static_cast<const char *>(q), *kcc = static_cast<const char *>(kc);
-    if (!IDENT && k_new != nullptr)
-        return (int)launch_kernel(score_kernel<BF16, false, true, kScoreWaves, kScoreBatches>, grid, block, 0, stream, ev,
-                                  qc, kcc, rep, H, k, T, Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats,
-                                  static_cast<const char *>(k_new));
-    return (int)launch_kernel(score_kernel<BF16, IDENT, false, kScoreWaves, kScoreBatches>, grid, block, 0, stream, ev, qc,
-                              kcc, rep, H, k, T, Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats, nullptr);
+    if constexpr (DT != DT_E4M3) {
+        if (!IDENT && k_new != nullptr)
+            return (int)launch_kernel(score_kernel<DT, false, true, kScoreWaves, kScoreBatches>, grid, block, 0, stream,
+                                      ev, qc, kcc, rep, H, k, T, Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats,
+                                      static_cast<const char *>(k_new), nullptr, q_dtype);
+    }
+    return (int)launch_kernel(score_kernel<DT, IDENT, false, kScoreWaves, kScoreBatches>, grid, block, 0, stream, ev, qc,
+                              kcc, rep, H, k, T, Tc_cap, scale, pl.cs, pl.n_cs, w.scores, w.stats, nullptr, kscale,
+                              q_dtype);
 }
 
 // A merge of the partial rows inside the value kernel (last workgroup of a head, found through a device-scope
@@ -458,26 +517,34 @@ int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H
 // phases (score workgroups first in the grid, value workgroups prefetching V and waiting on per-cluster
 // device-scope counters): 67 us against 55 us per LLaMa-7B layer -- cross-XCD flag traffic costs more than the
 // 2.5 us of a second launch.
-template <bool BF16, bool IDENT, int NW, int NB, int DS>
+template <int DT, bool IDENT, int NW, int NB, int DS>
 int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
-                  hipStream_t stream, const MemberRows *members, const void *v_new)
+                  hipStream_t stream, const MemberRows *members, const void *v_new, const float *vscale = nullptr)
 {
     // the copy of the probabilities (tests, inspection) lives in an instantiation of its own so that the
     // production kernel has no store inside its streaming loop; so does the variant that appends the new token
     const dim3 grid(pl.n_cp, H * DS, B), block(NW * 64);
     const char *vc = static_cast<const char *>(v);
-    hipError_t e;
-    if (!IDENT && v_new != nullptr)
-        e = launch_kernel(value_kernel<BF16, false, NW, NB, false, true, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H, k,
-                          T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out,
-                          static_cast<const char *>(v_new));
-    else if (probs_out != nullptr)
-        e = launch_kernel(value_kernel<BF16, IDENT, NW, NB, true, false, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H, k,
-                          T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out, nullptr);
+    hipError_t e = hipSuccess;
+    bool launched = false;
+    if constexpr (DT != DT_E4M3) {
+        if (!IDENT && v_new != nullptr) {
+            e = launch_kernel(value_kernel<DT, false, NW, NB, false, true, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H,
+                              k, T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out,
+                              static_cast<const char *>(v_new), nullptr);
+            launched = true;
+        }
+    }
+    if (launched) {
+    } else if (probs_out != nullptr)
+        e = launch_kernel(value_kernel<DT, IDENT, NW, NB, true, false, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H, k,
+                          T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out, nullptr,
+                          vscale);
     else
-        e = launch_kernel(value_kernel<BF16, IDENT, NW, NB, false, false, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H,
-                          k, T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out, nullptr);
+        e = launch_kernel(value_kernel<DT, IDENT, NW, NB, false, false, DS>, grid, block, 0, stream, ev, vc, h2c, rep, H,
+                          k, T, T_cap, pl.n_rec, pl.cp, pl.n_cp, w.scores, w.stats, w.partial, out, probs_out, nullptr,
+                          vscale);
     if (e != hipSuccess) return (int)e;
     if (members != nullptr)
         // one launch both adds the partial rows (n_cp = 1: the staged row itself) and hands them to the members
@@ -489,30 +556,37 @@ int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
                               out);
 }
 
-template <bool BF16, bool IDENT>
+template <int DT, bool IDENT>
 int values_typed(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                  float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
-                 hipStream_t stream, const MemberRows *members, const void *v_new)
+                 hipStream_t stream, const MemberRows *members, const void *v_new, const float *vscale = nullptr)
 {
+    if constexpr (DT == DT_E4M3) {
+        // rows of 8-bit codes are one cache line: no column split (the plan is made without it)
+        if (pl.cp >= 4096)
+            return values_launch<DT, IDENT, 4, 2, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new, vscale);
+        return values_launch<DT, IDENT, 8, 1, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new, vscale);
+    } else {
     // Workgroup shape (measured on MI355X): eight waves with one batch in flight each are 1-6 % faster than
     // four waves with two batches up to a few thousand tokens per workgroup; on long chunks four waves with
     // two batches are ~1.5 % ahead.
     const bool long_chunks = pl.cp >= 4096;
     if (pl.ds == 2) {
         if (long_chunks)
-            return values_launch<BF16, IDENT, 4, 2, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
-        return values_launch<BF16, IDENT, 8, 1, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+            return values_launch<DT, IDENT, 4, 2, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+        return values_launch<DT, IDENT, 8, 1, 2>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
     }
     if (long_chunks)
-        return values_launch<BF16, IDENT, 4, 2, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
-    return values_launch<BF16, IDENT, 8, 1, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+        return values_launch<DT, IDENT, 4, 2, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+    return values_launch<DT, IDENT, 8, 1, 1>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, pl, ev, stream, members, v_new);
+    }
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
 }  // namespace
 
-DecodePlan make_decode_plan(int B, int H, int k, int T)
+DecodePlan make_decode_plan(int B, int H, int k, int T, bool column_split)
 {
     DecodePlan pl;
     // Score chunk (measured on MI355X on the LLaMa-7B/33B, OPT-66B and 32k-context shapes): the largest of
@@ -532,7 +606,7 @@ DecodePlan make_decode_plan(int B, int H, int k, int T)
     // 2048 the token split is 3 % ahead again).
     {
         const long long heads = (long long)B * H > 0 ? (long long)B * H : 1;
-        pl.ds = (heads >= 192 && heads < 384 && T <= 1536) ? 2 : 1;
+        pl.ds = (column_split && heads >= 192 && heads < 384 && T <= 1536) ? 2 : 1;
         const long long groups = heads * pl.ds;
         long long want = groups >= 384 ? 1 : (1024 + groups - 1) / groups;
         const long long most = (T + 127) / 128;
@@ -561,10 +635,10 @@ int launch_scores(const void *q, const void *kc, const int32_t *rep, int B, int 
 {
     const Workspace w(workspace, plan);
     if (dtype == CHAI_BF16)
-        return identity ? scores_typed<true, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new)
-                        : scores_typed<true, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new);
-    return identity ? scores_typed<false, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new)
-                    : scores_typed<false, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new);
+        return identity ? scores_typed<DT_BF16, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new)
+                        : scores_typed<DT_BF16, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new);
+    return identity ? scores_typed<DT_F32, true>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new)
+                    : scores_typed<DT_F32, false>(q, kc, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, k_new);
 }
 
 int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
@@ -573,14 +647,32 @@ int launch_values(const void *v, const int32_t *h2c, const int32_t *rep, int B, 
 {
     const Workspace w(workspace, plan);
     if (dtype == CHAI_BF16)
-        return identity ? values_typed<true, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
-                                                   members, v_new)
-                        : values_typed<true, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
-                                                    members, v_new);
-    return identity ? values_typed<false, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
-                                                members, v_new)
-                    : values_typed<false, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
-                                                 members, v_new);
+        return identity ? values_typed<DT_BF16, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
+                                                      members, v_new)
+                        : values_typed<DT_BF16, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev,
+                                                       stream, members, v_new);
+    return identity ? values_typed<DT_F32, true>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
+                                                 members, v_new)
+                    : values_typed<DT_F32, false>(v, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream,
+                                                  members, v_new);
+}
+
+int launch_scores_q8(const void *q, int q_dtype, const void *k8, const float *kscale, const int32_t *rep, int B, int H,
+                     int k, int T, int Tc_cap, float scale, void *workspace, const DecodePlan &plan,
+                     const KernelEvents &ev, hipStream_t stream)
+{
+    const Workspace w(workspace, plan);
+    return scores_typed<DT_E4M3, false>(q, k8, rep, B, H, k, T, Tc_cap, scale, w, plan, ev, stream, nullptr, kscale,
+                                        q_dtype);
+}
+
+int launch_values_q8(const void *v8, const float *vscale, const int32_t *h2c, const int32_t *rep, int B, int H, int k,
+                     int T, int T_cap, float *out, float *probs_out, void *workspace, const DecodePlan &plan,
+                     const KernelEvents &ev, hipStream_t stream)
+{
+    const Workspace w(workspace, plan);
+    return values_typed<DT_E4M3, false>(v8, h2c, rep, B, H, k, T, T_cap, out, probs_out, w, plan, ev, stream, nullptr,
+                                        nullptr, vscale);
 }
 
 }  // namespace chai
