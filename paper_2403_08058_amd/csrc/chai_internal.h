@@ -8,6 +8,7 @@
 #include <stdint.h>
 
 #include "chai.h"
+#include "chai_probe.h"
 
 namespace chai {
 

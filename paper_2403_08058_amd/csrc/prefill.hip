@@ -26,9 +26,8 @@ namespace chai {
 
 namespace {
 
-constexpr int kGroup = 2;          // member heads that share one score tile in the 8-wave kernel
-constexpr int kWide = 4;           // ... and in the 4-wave kernel for larger clusters
-constexpr int kRec = 2 + kWide;    // ints per work-list record: cluster, member count, members
+constexpr int kGroup = 2;          // member heads that share one score tile
+constexpr int kRec = 2 + kGroup;   // ints per work-list record: cluster, member count, members
 constexpr int kQWave = 32;         // query rows per wave
 constexpr int kPWaves = 8;         // waves per workgroup (two per SIMD: one's MFMAs overlap the other's VALU work)
 constexpr int kPBlock = kPWaves * 64;
@@ -95,7 +94,7 @@ __global__ __launch_bounds__(256) void vt_kernel(const char *__restrict__ v, int
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// Work list: the heads of every cluster, in ascending order, cut into groups of at most `gsize` (<= kWide).
+// Work list: the heads of every cluster, in ascending order, cut into groups of at most `gsize` (<= kGroup).
 // groups[b][g] = {cluster, n, head_0 .. }, kRec ints per record; clusters in ascending order.  One workgroup per
 // batch row: the membership row is copied to LDS, thread j counts cluster j, thread h ranks head h among the
 // heads of its cluster, and every head writes its own slot.  Heads that name no live cluster are left out.
@@ -150,6 +149,13 @@ __global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t *__rest
 // ---------------------------------------------------------------------------------------------------------
 // Main kernel.  1-D grid of ceil(n_qt / 2) * n_slots * B workgroups of 512 threads; IDENT: every head is its own cluster
 // (dense attention) and the work list is not read.
+//
+// A score block is shared by the TWO members whose accumulators one wave can hold.  Sharing it among four -- the
+// two waves of a SIMD own the same 32 query rows and two members each, take turns producing the probabilities of
+// a 32-key block and hand them over through LDS in the B-operand layout, one barrier per block -- was built,
+// passed the same parity tests and measured SLOWER on the LLaMa-7B shape (670-840 us per 8-cluster layer in three
+// schedules against 578 us here): 128 query rows per workgroup double the staging per flop, every 32 keys cost a
+// workgroup barrier, and the producer's chain (scores -> softmax -> publish) is not hidden by its partner.
 //
 // Workgroup -> work item: the hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each with an L2
 // of its own.  The ids are therefore re-numbered so that every XCD owns a contiguous range of (batch row, group)
@@ -522,9 +528,9 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
                                  static_cast<const char *>(v), H, T_cap, n_keys, Tp, vt);
     if (e != hipSuccess) return (int)e;
     static DeviceFlags lds_ident, lds_clustered;
-    e = allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<true>), prefill_lds_bytes(true), lds_ident);
-    if (e != hipSuccess) return (int)e;
-    e = allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<false>), prefill_lds_bytes(false), lds_clustered);
+    e = identity ? allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<true>), prefill_lds_bytes(true), lds_ident)
+                 : allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<false>), prefill_lds_bytes(false),
+                                     lds_clustered);
     if (e != hipSuccess) return (int)e;
     // a workgroup takes a large and a small query tile, unless that leaves fewer than two workgroups per CU
     const bool paired = (long long)((n_qt + 1) / 2) * max_groups * B >= 512;

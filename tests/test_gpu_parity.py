@@ -456,3 +456,48 @@ def test_stream_read_probe_runs_and_checks_arguments():
     with pytest.raises(C.ChaiError) as e:
         C.chai_stream_read_probe(buf, sink, nbytes=24)                          # not a multiple of 16
     assert e.value.status == 2
+
+
+def test_out_of_range_map_entries_stay_contained():
+    """Device-side cluster maps cannot be checked on the host.  A corrupted entry (a cluster id or a representative
+    outside its range) must neither make a kernel touch memory outside the caller's tensors nor disturb the rows of
+    heads whose own entries are sound: the kernels clamp, and only the rows that depend on the bad entry change."""
+    B, H, kk, T, T_cap = 2, 32, 8, 700, 768
+    cfg = W.Config("corrupt", L=1, H=H, d=128, B=B, T=T, T_cap=T_cap, dtype=W.BF16, ks=(kk,), membership="random", seed=77)
+    x = W.layer_inputs(cfg, 0)
+    kd, vd, qd = dev(x.k), dev(x.v), dev(x.q)
+
+    def run(h2c_h, rep_h):
+        kc_whole, kc = G.guarded((B, kk, T_cap, 128), torch.bfloat16, 0.0)
+        C.chai_compact_kcache(kd, dev(rep_h), kc, T)
+        out_whole, out = G.guarded((B, H, 128), torch.float32, float("nan"))
+        ws = G.poisoned_workspace(B, H, kk, T, 128, cfg.dtype)
+        ws_guard = torch.full((ws.numel() + 2048,), 0x5A, dtype=torch.uint8, device="cuda")
+        off = (-ws_guard.data_ptr()) % 256 + 256
+        ws_in = ws_guard[off:off + ws.numel()]
+        ws_in.fill_(0xFF)
+        C.chai_decode_attention(qd, kc, vd, dev(h2c_h), dev(rep_h), T, cfg.scale, out, ws_in)
+        torch.cuda.synchronize()
+        assert G.guards_intact(kc_whole, (B, kk, T_cap, 128), 0.0)
+        assert G.guards_intact(out_whole, (B, H, 128), float("nan"))
+        assert bool((ws_guard[:off] == 0x5A).all()) and bool((ws_guard[off + ws.numel():] == 0x5A).all())
+        return out.cpu().numpy()
+
+    good = run(x.h2c, x.rep)
+    assert np.all(np.isfinite(good))
+    # 1. head (0, 3) names a cluster far outside [0, k); head (1, 5) a negative one
+    h2c_bad = x.h2c.copy()
+    h2c_bad[0, 3], h2c_bad[1, 5] = 9999, -7
+    got = run(h2c_bad, x.rep)
+    same = np.ones((B, H), bool)
+    same[0, 3] = same[1, 5] = False
+    assert np.array_equal(got[same], good[same])
+    assert np.all(np.isfinite(got))                      # clamped into range: some valid cluster's probabilities
+    # 2. the representative of cluster (0, 2) is a head id past H
+    rep_bad = x.rep.copy()
+    rep_bad[0, 2] = H + 100
+    got = run(x.h2c, rep_bad)
+    touched = np.zeros((B, H), bool)
+    touched[0] = x.h2c[0] == 2                            # only the members of that cluster see other scores
+    assert np.array_equal(got[~touched], good[~touched])
+    assert np.all(np.isfinite(got))
