@@ -734,7 +734,7 @@ def q8_bench(cfg, args, torch, C, W, steps, warmup, want_parity=True):
            "tokens_per_s": B / (ms * 1e-3), "ms_per_step": ms, "algorithmic_bytes_per_step": alg,
            "algorithmic_GBps": alg / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": alg / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
            "roofline": {"bound": "hbm", "kernel": "value_kernel (8-bit rows)", "achieved": ach, "peak": HBM_PEAK_GBS,
-                        "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": None, "bytes_per_launch": v_bytes,
+                        "unit": "GB/s", "frac": ach / HBM_PEAK_GBS, "traffic": read_traffic(cfg.name, "value_kernel_q8") if T == W.CONFIGS[cfg.name].T else None, "bytes_per_launch": v_bytes,
                         "avg_launch_ms": v_ms},
            "score_kernel_ms": s_ms, "host_wall_ms_per_step": wall_ms}
     if want_parity:
