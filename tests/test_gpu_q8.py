@@ -165,3 +165,41 @@ def test_q8_argument_errors():
     assert L.chai_quantize_rows(x.data_ptr(), 1, 0, 128, c.data_ptr(), s.data_ptr(), None) == 0
     assert C.chai_decode_q8_workspace_bytes(4, 72, 16, 2048) >= C.chai_decode_q8_workspace_bytes(4, 72, 16, 640) > 0
     assert C.chai_decode_q8_workspace_bytes(4, 72, 73, 2048) == 0
+
+
+def test_q8_full_size_sampled_heads():
+    """Quantised decode at the full LLaMa-7B-shaped size, in the launch configuration bench.py times: caches
+    quantised by the library, sampled (batch row, head) pairs checked against the oracle's own quantisation of the
+    bf16 rows and its attention over those codes."""
+    cfg = W.CONFIGS["cfg2"]
+    B, H, d, T, kk = cfg.B, cfg.H, cfg.d, cfg.T, 8
+    seed = cfg.seed * 4001
+    kc = W.device_normal((B, kk, T, d), cfg.dtype, seed)
+    v = W.device_normal((B, H, T, d), cfg.dtype, seed + 1)
+    q = W.device_normal((B, H, d), cfg.dtype, seed + 2)
+    h2c_h, rep_h = W.random_membership(W.rng(cfg.seed, 0, "member"), B, H, kk)
+    h2c, rep = dev(h2c_h), dev(rep_h)
+    print(f"[q8 full size] B={B} H={H} k={kk} T={T}", flush=True)
+    k8, ks = C.chai_quantize_rows(kc)
+    v8, vs = C.chai_quantize_rows(v)
+    out = torch.empty((B, H, d), dtype=torch.float32, device="cuda")
+    ws = torch.empty((C.chai_decode_q8_workspace_bytes(B, H, H, T),), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    C.chai_decode_attention_q8(q, k8, ks, v8, vs, h2c, rep, T, cfg.scale, out, ws)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(out).all())
+    g = np.random.default_rng(7)
+    for _ in range(12):
+        b, h = int(g.integers(B)), int(g.integers(H))
+        c = int(h2c_h[b, h])
+        kq, ksq = O.quantize_rows(W.torch_to_host_bits(kc[b, c]))
+        vq, vsq = O.quantize_rows(W.torch_to_host_bits(v[b, h]))
+        assert np.array_equal(kq, k8[b, c].cpu().numpy()) and np.array_equal(ksq, ks[b, c].cpu().numpy())
+        assert np.array_equal(vq, v8[b, h].cpu().numpy()) and np.array_equal(vsq, vs[b, h].cpu().numpy())
+        qr = W.torch_to_host_bits(q[b, rep_h[b, c]])
+        ref = O.clustered_decode_q8(np.stack([qr, qr * 0])[None], np.stack([kq, kq * 0])[None],
+                                    np.stack([ksq, ksq * 0])[None], np.stack([vq * 0, vq])[None],
+                                    np.stack([vsq * 0, vsq])[None], np.zeros((1, 2), np.int32),
+                                    np.zeros((1, 1), np.int32), T, cfg.scale)[0, 1]
+        ok, worst = G.rows_close(out[b, h].cpu().numpy()[None], ref[None], G.RTOL[cfg.dtype])
+        assert ok, f"(b={b}, h={h}): err/allowed {worst:.3g}"
