@@ -516,7 +516,12 @@ int scores_typed(const void *q, const void *kc, const int32_t *rep, int B, int H
 // still slower than the separate combine launch at every chunk count tried.  So was a single launch of both
 // phases (score workgroups first in the grid, value workgroups prefetching V and waiting on per-cluster
 // device-scope counters): 67 us against 55 us per LLaMa-7B layer -- cross-XCD flag traffic costs more than the
-// 2.5 us of a second launch.
+// 2.5 us of a second launch.  A third design -- one workgroup per (cluster, chunk of 128 tokens) that scores the
+// chunk, keeps exp(s - chunk max) in LDS and streams the chunk of every member's values, with a rescaling merge of
+// per-chunk partial rows as the only second launch -- needs no cross-workgroup wait at all and was slower still
+// (71 against 55 us per LLaMa-7B layer, 306 against 181 us at 32k tokens): thousands of short workgroups, each
+// with a dependent start-up chain (membership row -> member list -> values; keys -> scores -> two barriers), do
+// not stream like one long workgroup per head.
 template <int DT, bool IDENT, int NW, int NB, int DS>
 int values_launch(const void *v, const int32_t *h2c, const int32_t *rep, int B, int H, int k, int T, int T_cap,
                   float *out, float *probs_out, const Workspace &w, const DecodePlan &pl, const KernelEvents &ev,
