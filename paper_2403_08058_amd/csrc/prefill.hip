@@ -260,25 +260,34 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     // V^T in memory: blocks of 32 keys, [block][row][32 keys]; piece c of a 64-key row = block c/4, 16 B piece c%4
     const unsigned int v_off = (unsigned int)(((v_piece >> 2) * kHeadDim + v_row) * 64 + (v_piece & 3) * 16);
     // (the instruction exists only in the device pass of the compiler; the host pass sees an empty body)
-    auto load_to_lds = [](const char *src, char *dst) {
 #if defined(__HIP_DEVICE_COMPILE__)
-        __builtin_amdgcn_global_load_lds(src, (__attribute__((address_space(3))) void *)dst, 16, 0, 0);
-#else
-        (void)src;
-        (void)dst;
-#endif
+    typedef __amdgpu_buffer_rsrc_t Rsrc;
+    auto make_rsrc = [](const char *base) {
+        return __builtin_amdgcn_make_buffer_rsrc(const_cast<char *>(base), 0, 0x7fffffff, 0x00020000);
     };
+    auto load_to_lds = [](Rsrc rs, unsigned int off, char *dst) {
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (__attribute__((address_space(3))) void *)dst, 16, (int)off, 0, 0, 0);
+    };
+#else
+    typedef const char *Rsrc;
+    auto make_rsrc = [](const char *base) { return base; };
+    auto load_to_lds = [](Rsrc, unsigned int, char *) {};
+#endif
+    const Rsrc k_rs = make_rsrc(ksrc);
+    Rsrc v_rs[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) v_rs[g] = make_rsrc(vsrc[g]);
     auto dma_k = [&](int kt, int buf) {
         const int key0 = kt * kKTile;
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            load_to_lds(ksrc + ((size_t)min(key0 + k_row + 32 * i, n_keys - 1) * (kHeadDim * 2) + k_piece * 16),
+            load_to_lds(k_rs, (unsigned int)(min(key0 + k_row + 32 * i, n_keys - 1) * (kHeadDim * 2) + k_piece * 16),
                         k_lds + buf * kKBufBytes + (w + 8 * i) * 1024);
     };
     auto dma_v = [&](int kt, int g, int buf) {
 #pragma unroll
         for (int i = 0; i < 2; ++i)
-            load_to_lds(vsrc[g] + ((size_t)kt * (2 * kHeadDim * 64) + v_off + i * 64 * 64),
+            load_to_lds(v_rs[g], (unsigned int)kt * (2 * kHeadDim * 64) + v_off + i * 64 * 64,
                         v_lds + (buf * G + g) * kVBufBytes + (w + 8 * i) * 1024);
     };
     // The barrier of the tile loop: every wave first waits for its own requests (the compiler does not track loads
