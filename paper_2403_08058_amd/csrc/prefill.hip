@@ -15,7 +15,12 @@
 // row-major V cache cannot deliver, so a first kernel writes V^T once per call: fp16 (exact from bf16 inside
 // the fp16 range, |v| <= 65504), in blocks of 32 keys x 128 columns, keys permuted inside every group of 16 into
 // the order the probability registers have, zero beyond the last key.  The main kernel then stages K and V^T
-// tiles in LDS with plain 16-byte copies and feeds every MFMA operand with one ds_read_b128.
+// tiles in LDS with 16-byte direct loads and feeds every MFMA operand with one ds_read_b128.  (The LDS transpose
+// reads of this chip could hand the operand over from a row-major bf16 tile and make the pre-pass unnecessary,
+// but only as bf16: the probabilities would then be rounded to 8 bits as well, up to 2^-9 of relative error per
+// element, which is the whole error budget of the 16-bit contract; converting the values to fp16 inside the
+// main kernel instead would be paid by every workgroup that streams a tile, a dozen vector instructions per
+// MFMA.)
 #include "chai_internal.h"
 
 #include <hip/hip_ext.h>
@@ -150,12 +155,21 @@ __global__ __launch_bounds__(256) void prefill_plan_kernel(const int32_t *__rest
 // Main kernel.  1-D grid of ceil(n_qt / 2) * n_slots * B workgroups of 512 threads; IDENT: every head is its own cluster
 // (dense attention) and the work list is not read.
 //
-// A score block is shared by the TWO members whose accumulators one wave can hold.  Sharing it among four -- the
-// two waves of a SIMD own the same 32 query rows and two members each, take turns producing the probabilities of
-// a 32-key block and hand them over through LDS in the B-operand layout, one barrier per block -- was built,
-// passed the same parity tests and measured SLOWER on the LLaMa-7B shape (670-840 us per 8-cluster layer in three
-// schedules against 578 us here): 128 query rows per workgroup double the staging per flop, every 32 keys cost a
-// workgroup barrier, and the producer's chain (scores -> softmax -> publish) is not hidden by its partner.
+// A score block is shared by the TWO members whose accumulators one wave can hold.  Two wider schemes were built,
+// passed the same parity tests and measured no faster on the LLaMa-7B shape, so neither is kept:
+//  * four members through LDS -- the two waves of a SIMD own the same 32 query rows and two members each, take
+//    turns producing the probabilities of a 32-key block and hand them over in the B-operand layout, one barrier
+//    per block: 670-840 us per 8-cluster layer in three schedules against 578 us for pairs (128 query rows per
+//    workgroup double the staging per flop, and the producer's chain scores -> softmax -> publish is not hidden
+//    by its partner);
+//  * three members in ONE wave -- four waves per workgroup, one per SIMD, 192 accumulation registers of
+//    accumulators (a fourth member does not fit: the compiler keeps every MFMA result, the score block's
+//    included, in the accumulation half), the loop software-pipelined by hand (value products of block i-1, score
+//    product of block i+1 and softmax of block i interleaved instruction by instruction, LDS fragments four
+//    MFMAs ahead, rings of three 32-key blocks): equal to pairs when every cluster has exactly three heads
+//    (592 against 596 us), 630 us against 553 us on the benchmark's membership and 1000 against 730 us when
+//    every head is its own cluster.  A single wave per SIMD issues about eight vector instructions per MFMA and
+//    nothing else fills its waits.
 //
 // Workgroup -> work item: the hardware deals consecutive workgroup ids round-robin to the 8 XCDs, each with an L2
 // of its own.  The ids are therefore re-numbered so that every XCD owns a contiguous range of (batch row, group)
@@ -243,13 +257,19 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         for (int ks = 0; ks < kHeadDim / 16; ++ks) qf[ks].raw = *reinterpret_cast<const u32x4 *>(qrow + ks * 32);
     }
 
-    // Staging with direct global -> LDS loads: one instruction moves 64 pieces of 16 bytes into 1 KB of consecutive
-    // LDS (lane l's piece lands at base + 16 l), no registers and no LDS write instructions.  Rows are therefore
-    // unpadded, and bank conflicts of the fragment reads are avoided by a swizzle instead: piece c of K row R sits
-    // in slot c ^ (R & 15) of the row, piece c of V^T row R in slot c ^ ((R >> 1) & 7); 16 consecutive rows read at
-    // one piece index then touch 16 different 16-byte slots of the 256-byte bank window.  A lane fetches whichever
+    // Staging with direct loads to LDS: one instruction moves 64 pieces of 16 bytes into 1 KB of consecutive LDS
+    // (lane l's piece lands at base + 16 l), no registers and no LDS write instructions.  The BUFFER form of the
+    // instruction is used: with the global form in a loop the compiler gives up counting LDS reads and waits for
+    // all of them (lgkmcnt(0)) before every MFMA; with the buffer form it waits for exactly the fragment it needs
+    // (measured 4-5 % faster, and the register allocation no longer spills).  Rows are unpadded, and bank
+    // conflicts of the fragment reads are avoided by a swizzle instead: piece c of K row R sits in slot
+    // c ^ (R & 15) of the row, piece c of V^T row R in slot c ^ ((R >> 1) & 7); 16 consecutive rows read at one
+    // piece index then touch 16 different 16-byte slots of the 256-byte bank window.  A lane fetches whichever
     // piece belongs in the slot it fills.  Wave w fills K rows 4w..4w+3 and 32+4w.. (two instructions per tile)
     // and V^T rows 8w..8w+7 and 64+8w.. of every member (two instructions per member and tile).
+    // Requesting the tiles one iteration earlier still (rings of six K half-tiles and three V^T tiles, the wait
+    // before the barrier leaving the newest requests in flight) was measured too: no gain (565 against 553 us),
+    // the loop does not wait for these loads.
     const char *ksrc = kc + ((size_t)b * k + cluster) * (size_t)Tc_cap * (kHeadDim * 2);
     const char *vsrc[G];
 #pragma unroll
