@@ -32,6 +32,7 @@ namespace chai {
 namespace {
 
 constexpr int kGroup = 2;          // member heads that share one score tile
+constexpr int kPairedRounds = 4;     // launches of fewer rounds of 256 paired workgroups send single tiles instead
 constexpr int kRec = 2 + kGroup;   // ints per work-list record: cluster, member count, members
 constexpr int kQWave = 32;         // query rows per wave
 constexpr int kPWaves = 8;         // waves per workgroup (two per SIMD: one's MFMAs overlap the other's VALU work)
@@ -193,7 +194,7 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
                                                           const int32_t *__restrict__ groups,
                                                           const int32_t *__restrict__ n_groups, int H, int k, int Tq,
                                                           int q_start, int Tc_cap, int Tp, int n_qt_arg, int n_slots,
-                                                          float scale, float *__restrict__ out)
+                                                          int n_rows, float scale, float *__restrict__ out)
 {
     constexpr int G = IDENT ? 1 : kGroup;
     extern __shared__ __attribute__((aligned(1024))) char lds_raw[];
@@ -206,12 +207,14 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
     // A work item is a PAIR of query tiles, the p-th largest and the p-th smallest of a group: under the causal
     // mask tile q walks q+1 key tiles' worth of work, so every pair costs the same and the workgroups of a launch
     // finish together instead of leaving a tail of long ones.
-    // (n_qt < 0: the launch is too small to fill the chip with pairs; every tile is then an item of its own.)
+    // (n_qt < 0: a small launch; every tile is then an item of its own, see the numbering above.  On launches of
+    // many rounds single tiles measured 3-8 % SLOWER than pairs: the tiles of a group no longer run side by side and
+    // stop sharing its keys and values in L2.)
     const bool paired = n_qt_arg > 0;
     const int n_qt = paired ? n_qt_arg : -n_qt_arg;
     const int n_pairs = paired ? (n_qt + 1) / 2 : n_qt;
     int pi, gi, b;
-    {
+    if (paired) {
         const unsigned n = blockIdx.x, N = gridDim.x;
         const unsigned x = n & 7u, per = N >> 3, rem = N & 7u;
         const unsigned item = x * per + min(x, rem) + (n >> 3);
@@ -219,6 +222,17 @@ __global__ __launch_bounds__(kPBlock) void prefill_kernel(const char *__restrict
         const unsigned rest = item / (unsigned)n_pairs;
         gi = (int)(rest % (unsigned)n_slots);
         b = (int)(rest / (unsigned)n_slots);
+    } else {
+        // single tiles, the largest first: XCD x owns `per_xcd` consecutive (batch row, group) slots, and its
+        // workgroups come in the order tile n_qt-1 of every slot, then tile n_qt-2 of every slot, ...; the hardware
+        // hands the next workgroup to the first CU that is free, which is longest-job-first list scheduling
+        const unsigned n = blockIdx.x, x = n & 7u, local = n >> 3;
+        const unsigned per_xcd = gridDim.x / (8u * (unsigned)n_qt);
+        const unsigned slot = x * per_xcd + local % per_xcd;
+        if (slot >= (unsigned)(n_slots * n_rows)) return;
+        pi = (int)(local / per_xcd);
+        gi = (int)(slot % (unsigned)n_slots);
+        b = (int)(slot / (unsigned)n_slots);
     }
 
     int cluster, n_mem, heads[G];
@@ -561,23 +575,26 @@ int launch_prefill(const void *q, const void *kc, const void *v, const int32_t *
                  : allow_dynamic_lds(reinterpret_cast<const void *>(&prefill_kernel<false>), prefill_lds_bytes(false),
                                      lds_clustered);
     if (e != hipSuccess) return (int)e;
-    // a workgroup takes a large and a small query tile, unless that leaves fewer than two workgroups per CU
-    const bool paired = (long long)((n_qt + 1) / 2) * max_groups * B >= 512;
-    const int n_pairs = paired ? (n_qt + 1) / 2 : n_qt;
+    // A workgroup takes a large and a small query tile (equal work for all), unless the launch is small: below
+    // kPairedRounds rounds of the chip a partly filled last round of equal workgroups costs more than pairing
+    // gains, and the tiles go out singly, the largest first.
+    const bool paired = (long long)((n_qt + 1) / 2) * max_groups * B >= (long long)kPairedRounds * 256;
     const int n_qt_arg = paired ? n_qt : -n_qt;
-    if ((long long)n_pairs * max_groups * B > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
-    const unsigned int n_wg = (unsigned int)n_pairs * (unsigned int)max_groups * (unsigned int)B;
+    const long long slots = (long long)max_groups * B;
+    const long long n_wg_ll = paired ? (long long)((n_qt + 1) / 2) * slots : 8LL * n_qt * ((slots + 7) / 8);
+    if (n_wg_ll > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    const unsigned int n_wg = (unsigned int)n_wg_ll;
     if (identity) {
         return (int)launch_kernel(prefill_kernel<true>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(true), stream, ev,
                                   static_cast<const char *>(q), static_cast<const char *>(kc), vt, nullptr, nullptr,
-                                  nullptr, H, k, Tq, q_start, Tc_cap, Tp, n_qt_arg, max_groups, scale, out);
+                                  nullptr, H, k, Tq, q_start, Tc_cap, Tp, n_qt_arg, max_groups, B, scale, out);
     }
     e = launch_kernel(prefill_plan_kernel, dim3(B), dim3(256), (size_t)(H + 2 * k) * sizeof(int32_t), stream,
                       KernelEvents(), h2c, rep, H, k, kGroup, max_groups, groups, n_groups);
     if (e != hipSuccess) return (int)e;
     return (int)launch_kernel(prefill_kernel<false>, dim3(n_wg), dim3(kPBlock), prefill_lds_bytes(false), stream, ev,
                               static_cast<const char *>(q), static_cast<const char *>(kc), vt, rep, groups, n_groups, H, k,
-                              Tq, q_start, Tc_cap, Tp, n_qt_arg, max_groups, scale, out);
+                              Tq, q_start, Tc_cap, Tp, n_qt_arg, max_groups, B, scale, out);
 }
 
 }  // namespace chai
