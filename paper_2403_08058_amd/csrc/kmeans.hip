@@ -13,15 +13,6 @@ namespace chai {
 
 namespace {
 
-__device__ __forceinline__ double load_elem(const void *base, size_t idx, bool bf16)
-{
-    if (bf16) {
-        const unsigned int w = (unsigned int)static_cast<const unsigned short *>(base)[idx] << 16;
-        return (double)__uint_as_float(w);
-    }
-    return (double)static_cast<const float *>(base)[idx];
-}
-
 // ---------------------------------------------------------------------------------------------------------
 // Features: grid (H, B), one wave per head.  Lane p < n_tok*(n_tok+1)/2 owns one causal (i, j) pair and runs
 // its 128-term dot product in element order in fp64; lane i < n_tok then normalises row i.
@@ -40,10 +31,37 @@ __global__ __launch_bounds__(64) void feature_kernel(const void *__restrict__ q5
     if (i < n_tok) {
         const size_t qo = head * (size_t)qs + (size_t)i * kHeadDim;
         const size_t ko = head * (size_t)ks + (size_t)j * kHeadDim;
+        // 16-byte loads (rows start on 16-byte boundaries: the strides are multiples of 8 elements); the products
+        // are still added one by one in element order
         double acc = 0.0;
-        for (int c = 0; c < kHeadDim; ++c) {
-            const double prod = load_elem(q5, qo + c, bf16) * load_elem(k5, ko + c, bf16);
-            acc = acc + prod;
+        if (bf16) {
+            const uint4 *qv = reinterpret_cast<const uint4 *>(static_cast<const unsigned short *>(q5) + qo);
+            const uint4 *kv = reinterpret_cast<const uint4 *>(static_cast<const unsigned short *>(k5) + ko);
+#pragma unroll 4
+            for (int c8 = 0; c8 < kHeadDim / 8; ++c8) {
+                const uint4 a = qv[c8], bb = kv[c8];
+                const unsigned int aw[4] = {a.x, a.y, a.z, a.w}, bw[4] = {bb.x, bb.y, bb.z, bb.w};
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const unsigned int abits = (e & 1) ? (aw[e >> 1] & 0xffff0000u) : (aw[e >> 1] << 16);
+                    const unsigned int bbits = (e & 1) ? (bw[e >> 1] & 0xffff0000u) : (bw[e >> 1] << 16);
+                    const double prod = (double)__uint_as_float(abits) * (double)__uint_as_float(bbits);
+                    acc = acc + prod;
+                }
+            }
+        } else {
+            const float4 *qv = reinterpret_cast<const float4 *>(static_cast<const float *>(q5) + qo);
+            const float4 *kv = reinterpret_cast<const float4 *>(static_cast<const float *>(k5) + ko);
+#pragma unroll 4
+            for (int c4 = 0; c4 < kHeadDim / 4; ++c4) {
+                const float4 a = qv[c4], bb = kv[c4];
+                const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {bb.x, bb.y, bb.z, bb.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const double prod = (double)av[e] * (double)bv[e];
+                    acc = acc + prod;
+                }
+            }
         }
         s[i][j] = scale * acc;
     }
@@ -72,6 +90,23 @@ __device__ __forceinline__ double sqdist(const float *__restrict__ x, const doub
         const double diff = (double)x[f] - c[f];
         const double sq = diff * diff;
         acc = acc + sq;
+    }
+    return acc;
+}
+
+// The same sum with the head's coordinates in registers: every term in index order, terms past F left out.  Fully
+// unrolled, so the loads of the centre's coordinates are all in flight together instead of one per iteration.
+constexpr int kRegF = 32;
+__device__ __forceinline__ double sqdist_regs(const double (&x)[kRegF], const double *c, int F)
+{
+    double acc = 0.0;
+#pragma unroll
+    for (int f = 0; f < kRegF; ++f) {
+        if (f < F) {
+            const double diff = x[f] - c[f];
+            const double sq = diff * diff;
+            acc = acc + sq;
+        }
     }
     return acc;
 }
@@ -109,6 +144,13 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
     for (int h = tid; h < H; h += kBlock) prev[h] = -1;
     __syncthreads();
 
+    // H * slices <= kBlock: a thread keeps the same (head, slice) in every pass, so the head's coordinates are
+    // converted once and stay in registers when there are few enough of them
+    const bool in_regs = F <= kRegF && tid < H * slices;
+    double xr[kRegF];
+#pragma unroll
+    for (int f = 0; f < kRegF; ++f) xr[f] = (in_regs && f < F) ? (double)Xg[(size_t)(tid / slices) * F + f] : 0.0;
+
     int it = 0;
     for (;;) {
         ++it;
@@ -122,7 +164,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
             int best = -1;
             double bd = 0.0;
             for (int j = sl; j < k; j += slices) {
-                const double dj = sqdist(x, centre + (size_t)j * F, F);
+                const double dj = in_regs ? sqdist_regs(xr, centre + (size_t)j * F, F) : sqdist(x, centre + (size_t)j * F, F);
                 if (best < 0 || dj < bd) { bd = dj; best = j; }
             }
             cand_d[p] = bd;
@@ -145,6 +187,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
         int empty = 0;
         for (int j = tid; j < k; j += kBlock) {
             int n = 0;
+#pragma unroll 8
             for (int h = 0; h < H; ++h) n += assign[h] == j;
             count[j] = n;
             empty |= n == 0;
@@ -181,6 +224,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
             int at = 0;
             for (int i = 0; i < j; ++i) at += count[i];
             first[j] = at;
+#pragma unroll 8
             for (int h = 0; h < H; ++h)
                 if (assign[h] == j) order[at++] = h;
         }
@@ -192,6 +236,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
             if (n == 0) continue;
             const int *mem = order + first[j];
             double acc = 0.0;
+#pragma unroll 4
             for (int m = 0; m < n; ++m) acc = acc + (double)X[(size_t)mem[m] * F + f];
             centre[i] = acc / (double)n;
         }
