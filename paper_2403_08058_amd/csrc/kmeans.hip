@@ -79,7 +79,7 @@ __global__ __launch_bounds__(64) void feature_kernel(const void *__restrict__ q5
 }
 
 // ---------------------------------------------------------------------------------------------------------
-// K-Means: grid (B), one workgroup of 256 threads per batch row.  Dynamic LDS: centres [k][F] fp64, per-head
+// K-Means: grid (B), one workgroup of 512 threads per batch row.  Dynamic LDS: centres [k][F] fp64, per-head
 // distance [H] fp64, slice winners [H][slices], assignment/previous assignment/member order [H],
 // counts/labels/list starts [k], and a copy of the features when it fits.
 // ---------------------------------------------------------------------------------------------------------
@@ -97,6 +97,7 @@ __device__ __forceinline__ double sqdist(const float *__restrict__ x, const doub
 // The same sum with the head's coordinates in registers: every term in index order, terms past F left out.  Fully
 // unrolled, so the loads of the centre's coordinates are all in flight together instead of one per iteration.
 constexpr int kRegF = 32;
+constexpr int kKmBlock = 512;        // threads of the k-means workgroup: more slices per head, one round for the update
 __device__ __forceinline__ double sqdist_regs(const double (&x)[kRegF], const double *c, int F)
 {
     double acc = 0.0;
@@ -111,7 +112,7 @@ __device__ __forceinline__ double sqdist_regs(const double (&x)[kRegF], const do
     return acc;
 }
 
-__global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict__ feat, int H, int F, int k,
+__global__ __launch_bounds__(kKmBlock) void kmeans_kernel(const float *__restrict__ feat, int H, int F, int k,
                                                         const int32_t *__restrict__ init_heads, int max_iter,
                                                         int slices, int stage_x, int32_t *__restrict__ h2c,
                                                         int32_t *__restrict__ rep, int32_t *__restrict__ ncl,
@@ -133,18 +134,18 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
     const int b = blockIdx.x, tid = threadIdx.x;
     const float *Xg = feat + (size_t)b * H * F;
     if (stage_x)
-        for (int i = tid; i < H * F; i += kBlock) x_lds[i] = Xg[i];
+        for (int i = tid; i < H * F; i += kKmBlock) x_lds[i] = Xg[i];
     const float *X = stage_x ? x_lds : Xg;                  // same values either way
 
-    for (int i = tid; i < k * F; i += kBlock) {
+    for (int i = tid; i < k * F; i += kKmBlock) {
         const int j = i / F, f = i - j * F;
         const int h0 = min(max(init_heads[(size_t)b * k + j], 0), H - 1);
         centre[i] = (double)Xg[(size_t)h0 * F + f];
     }
-    for (int h = tid; h < H; h += kBlock) prev[h] = -1;
+    for (int h = tid; h < H; h += kKmBlock) prev[h] = -1;
     __syncthreads();
 
-    // H * slices <= kBlock: a thread keeps the same (head, slice) in every pass, so the head's coordinates are
+    // H * slices <= kKmBlock: a thread keeps the same (head, slice) in every pass, so the head's coordinates are
     // converted once and stay in registers when there are few enough of them
     const bool in_regs = F <= kRegF && tid < H * slices;
     double xr[kRegF];
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
         // ascending order and keeps the first smallest), then one thread per head picks the smallest of the
         // slice winners, the lowest centre on ties: the same centre a single ascending scan would pick.  Each
         // distance is one sequential fp64 sum inside one thread.
-        for (int p = tid; p < H * slices; p += kBlock) {
+        for (int p = tid; p < H * slices; p += kKmBlock) {
             const int h = p / slices, sl = p - h * slices;
             const float *x = X + (size_t)h * F;
             int best = -1;
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
             cand_j[p] = best;
         }
         __syncthreads();
-        for (int h = tid; h < H; h += kBlock) {
+        for (int h = tid; h < H; h += kKmBlock) {
             int best = cand_j[(size_t)h * slices];
             double bd = cand_d[(size_t)h * slices];
             for (int sl = 1; sl < slices; ++sl) {
@@ -185,7 +186,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
         __syncthreads();
         // members per centre: thread j counts centre j (integers: any order gives the sequential result)
         int empty = 0;
-        for (int j = tid; j < k; j += kBlock) {
+        for (int j = tid; j < k; j += kKmBlock) {
             int n = 0;
 #pragma unroll 8
             for (int h = 0; h < H; ++h) n += assign[h] == j;
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
             __syncthreads();
         }
         int moved = 0;
-        for (int h = tid; h < H; h += kBlock) {
+        for (int h = tid; h < H; h += kKmBlock) {
             moved |= assign[h] != prev[h];
             prev[h] = assign[h];
         }
@@ -220,7 +221,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
         if (!changed || it >= max_iter) break;
         // member lists: thread j writes the heads of centre j, in ascending order, behind those of the centres
         // before it
-        for (int j = tid; j < k; j += kBlock) {
+        for (int j = tid; j < k; j += kKmBlock) {
             int at = 0;
             for (int i = 0; i < j; ++i) at += count[i];
             first[j] = at;
@@ -230,7 +231,7 @@ __global__ __launch_bounds__(kBlock) void kmeans_kernel(const float *__restrict_
         }
         __syncthreads();
         // update: one thread per (centre, coordinate), members added in head order
-        for (int i = tid; i < k * F; i += kBlock) {
+        for (int i = tid; i < k * F; i += kKmBlock) {
             const int j = i / F, f = i - j * F;
             const int n = count[j];
             if (n == 0) continue;
@@ -327,7 +328,7 @@ __global__ __launch_bounds__(kBlock) void cluster_error_kernel(const float *__re
 // threads that share the centres of one head: as many as fit the workgroup, at most one per centre
 int assignment_slices(int H, int k)
 {
-    int s = kBlock / H;
+    int s = kKmBlock / H;
     if (s > k) s = k;
     return s < 1 ? 1 : s;
 }
@@ -359,7 +360,7 @@ int launch_assign_clusters(const float *feat, int B, int H, int F, int k, const 
                            int32_t *h2c, int32_t *rep, int32_t *ncl, int32_t *iters, hipStream_t stream)
 {
     const size_t copy = kmeans_feature_copy_bytes(H, F, k);
-    return (int)launch_kernel(kmeans_kernel, dim3(B), dim3(kBlock), assign_clusters_lds_bytes(H, F, k) + copy, stream,
+    return (int)launch_kernel(kmeans_kernel, dim3(B), dim3(kKmBlock), assign_clusters_lds_bytes(H, F, k) + copy, stream,
                               KernelEvents(), feat, H, F, k, init_heads, max_iter, assignment_slices(H, k),
                               copy != 0 ? 1 : 0, h2c, rep, ncl, iters);
 }
