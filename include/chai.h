@@ -432,7 +432,8 @@ int chai_dense_decode_attention(const void *q, const void *k_cache, const void *
  *   workspace chai_prefill_workspace_bytes(B,H,k,q_start+Tq) bytes, 256-byte
  *             aligned (holds the work list and a transposed fp16 copy of the
  *             values, B*H*d*roundup(q_start+Tq,64)*2 bytes)
- * q_start + Tq <= min(T_cap, Tc_cap), Tq >= 1, q_start >= 0, H <= 4096.
+ * q_start + Tq <= min(T_cap, Tc_cap), Tq >= 1, q_start >= 0, H <= 4096, q_start + Tq <= 2^23 - 64 (one head's
+ * keys are addressed with 32-bit byte offsets; beyond that CHAI_ERR_UNSUPPORTED).
  *
  * chai_dense_prefill_attention: the dense baseline (every head its own
  * cluster, K read in place), same kernel.

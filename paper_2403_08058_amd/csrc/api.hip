@@ -509,6 +509,8 @@ static int check_prefill(const void *q, const void *kc, const void *v, const flo
     if (B < 0 || H < 1 || k < 1 || k > H || Tq < 1 || q_start < 0 || d < 1) return CHAI_ERR_SHAPE;
     if ((long long)q_start + Tq > T_cap || (long long)q_start + Tq > Tc_cap) return CHAI_ERR_SHAPE;
     if (d != kHeadDim || dtype != CHAI_BF16 || B > kMaxGridYZ || H > 4096 || !(scale > 0.f)) return CHAI_ERR_UNSUPPORTED;
+    // the kernel addresses one head's keys and transposed values with 32-bit byte offsets below 2 GiB
+    if ((long long)q_start + Tq > (1LL << 23) - 64) return CHAI_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(kc) || !aligned16(v) || !aligned16(out)) return CHAI_ERR_ALIGN;
     if (B > 0 && (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) != 0 ||
                   workspace_bytes < prefill_workspace_bytes(B, H, k, q_start + Tq)))

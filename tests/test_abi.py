@@ -99,6 +99,7 @@ def test_argument_checks_run_before_any_launch(chai):
     assert pf(scale=0.0) == 5 and pf(scale=-0.1) == 5 and pf(scale=float("nan")) == 5
     assert pf(q=fake + 2) == 7
     assert pf(B=0) == 0                         # empty batch: no-op
+    assert pf(Tq=1 << 23, Tc_cap=1 << 23, T_cap=1 << 23, ws_bytes=1 << 60) == 5     # beyond 32-bit key offsets
     assert L.chai_dense_prefill_attention(fake, fake, fake, 1, 32, 64, 0, 64, 128, 1, -1.0, fake, 0x1000, big, None) == 5
     # projections of the representatives: x [B,Tn,D], weights [H*d, D]
     pj = lambda **kw: L.chai_project_qk(*[kw.get(n, dflt) for n, dflt in (
