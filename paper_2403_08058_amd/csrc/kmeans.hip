@@ -97,6 +97,7 @@ __device__ __forceinline__ double sqdist(const float *__restrict__ x, const doub
 // The same sum with the head's coordinates in registers: every term in index order, terms past F left out.  Fully
 // unrolled, so the loads of the centre's coordinates are all in flight together instead of one per iteration.
 constexpr int kRegF = 32;
+constexpr int kHeadWaves = 4;         // waves that own a head each (H <= 256)
 constexpr int kKmBlock = 512;        // threads of the k-means workgroup: more slices per head, one round for the update
 __device__ __forceinline__ double sqdist_regs(const double (&x)[kRegF], const double *c, int F)
 {
@@ -129,7 +130,8 @@ __global__ __launch_bounds__(kKmBlock) void kmeans_kernel(const float *__restric
     int *label = count + k;                                 // [k]
     int *order = label + k;                                 // [H] heads sorted by centre, ascending inside a centre
     int *first = order + H;                                 // [k] where a centre's heads start in `order`
-    float *x_lds = reinterpret_cast<float *>(first + k);    // [H][F] copy of the features, when it fits
+    int *wave_count = first + k;                            // [kHeadWaves][k] heads of a centre inside one wave
+    float *x_lds = reinterpret_cast<float *>(wave_count + kHeadWaves * k);   // [H][F] copy of the features, when it fits
 
     const int b = blockIdx.x, tid = threadIdx.x;
     const float *Xg = feat + (size_t)b * H * F;
@@ -183,16 +185,14 @@ __global__ __launch_bounds__(kKmBlock) void kmeans_kernel(const float *__restric
             assign[h] = best;
             dmin[h] = bd;
         }
+        for (int j = tid; j < k; j += kKmBlock) count[j] = 0;
         __syncthreads();
-        // members per centre: thread j counts centre j (integers: any order gives the sequential result)
+        // members per centre: every head adds one to its centre's counter (integers: any order gives the
+        // sequential result)
+        for (int h = tid; h < H; h += kKmBlock) atomicAdd(&count[assign[h]], 1);
+        __syncthreads();
         int empty = 0;
-        for (int j = tid; j < k; j += kKmBlock) {
-            int n = 0;
-#pragma unroll 8
-            for (int h = 0; h < H; ++h) n += assign[h] == j;
-            count[j] = n;
-            empty |= n == 0;
-        }
+        for (int j = tid; j < k; j += kKmBlock) empty |= count[j] == 0;
         // Centres that received no head take, in ascending order, the farthest head of a cluster that can spare
         // one.  Sequential by nature, but needed only when some centre is empty.
         if (__syncthreads_or(empty)) {
@@ -219,15 +219,31 @@ __global__ __launch_bounds__(kKmBlock) void kmeans_kernel(const float *__restric
         }
         const int changed = __syncthreads_or(moved);        // same value in every thread
         if (!changed || it >= max_iter) break;
-        // member lists: thread j writes the heads of centre j, in ascending order, behind those of the centres
-        // before it
-        for (int j = tid; j < k; j += kKmBlock) {
-            int at = 0;
-            for (int i = 0; i < j; ++i) at += count[i];
-            first[j] = at;
-#pragma unroll 8
-            for (int h = 0; h < H; ++h)
-                if (assign[h] == j) order[at++] = h;
+        // member lists: the heads of centre j in ascending order, behind those of the centres before it.  Thread h
+        // owns head h (H <= 256: the first four waves); its place is the number of lower heads of the same centre,
+        // counted with one wave vote per centre plus the totals of the waves before it.
+        {
+            const int wv = tid >> 6, ln = tid & 63;
+            const int a = tid < H ? assign[tid] : -1;
+            int below = 0;
+            if (wv < kHeadWaves) {
+                for (int j = 0; j < k; ++j) {
+                    const unsigned long long votes = __ballot(a == j);
+                    if (a == j) below = __popcll(votes & ((1ull << ln) - 1ull));
+                    if (ln == 0) wave_count[wv * k + j] = __popcll(votes);
+                }
+            }
+            for (int j = tid; j < k; j += kKmBlock) {
+                int at = 0;
+                for (int i = 0; i < j; ++i) at += count[i];
+                first[j] = at;
+            }
+            __syncthreads();
+            if (tid < H) {
+                int at = first[a] + below;
+                for (int i = 0; i < wv; ++i) at += wave_count[i * k + a];
+                order[at] = tid;
+            }
         }
         __syncthreads();
         // update: one thread per (centre, coordinate), members added in head order
@@ -345,7 +361,8 @@ int launch_score_features(const void *q5, const void *k5, int B, int H, int n_to
 size_t assign_clusters_lds_bytes(int H, int F, int k)
 {
     const size_t sl = (size_t)assignment_slices(H, k);
-    return sizeof(double) * ((size_t)k * F + H + H * sl) + sizeof(int) * (H * sl + 3 * (size_t)H + 3 * (size_t)k);
+    return sizeof(double) * ((size_t)k * F + H + H * sl) +
+           sizeof(int) * (H * sl + 3 * (size_t)H + (3 + kHeadWaves) * (size_t)k);
 }
 
 // the features are copied to LDS too when that still fits the 64 KB a workgroup may ask for
