@@ -56,7 +56,8 @@ def run_case(B, H, kk, Tq, q_start, T_cap, seed, membership="random", sizes=None
     (2, 52, 4, 64, 100, 200),      # block in the middle of the sequence
     (1, 72, 16, 1, 40, 64),        # a single query row
     (1, 4, 1, 129, 31, 192),       # one cluster for all heads
-    (16, 32, 8, 640, 5, 645),      # large enough for paired query tiles, odd tile count (the middle one alone)
+    (16, 32, 8, 640, 5, 645),      # three query tiles sent singly, the largest first
+    (22, 32, 8, 640, 5, 645),      # enough workgroups for paired query tiles, odd tile count (the middle one alone)
 ])
 def test_prefill_matches_oracle(B, H, kk, Tq, q_start, T_cap):
     worst, _ = run_case(B, H, kk, Tq, q_start, T_cap, seed=B * 31 + H * 7 + Tq)
