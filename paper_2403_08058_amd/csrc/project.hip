@@ -121,6 +121,9 @@ __global__ __launch_bounds__(kJBlock) void project_kernel(const char *__restrict
         if (s + 1 < n_steps) stage(buf ^ 1);          // fetched one iteration ago
         if (s + 2 < n_steps) fetch(s + 2);
         const char *base = lds + buf * kJTileBytes;
+        // scheduling hint: spread the LDS reads and the stage's global loads and LDS writes between the MFMAs of
+        // the step instead of grouping them (measured: about 2 % faster)
+        __builtin_amdgcn_iglp_opt(1);
 #pragma unroll
         for (int ks = 0; ks < kJStep / 16; ++ks) {
             Frag af[4], bfr[2];
