@@ -83,7 +83,8 @@ __global__ __launch_bounds__(256) void vt_kernel(const char *__restrict__ v, int
         const int piece = tid + i * 256, jj = piece >> 4, c8 = piece & 15;       // key row, 8-column block
         Frag16 x;
         x.raw = u32x4{0u, 0u, 0u, 0u};
-        if (t0 + jj < n_keys) x.raw = *reinterpret_cast<const u32x4 *>(vhead + (size_t)(t0 + jj) * (kHeadDim * 2) + c8 * 16);
+        if (t0 + jj < n_keys)
+            x.raw = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vhead + (size_t)(t0 + jj) * (kHeadDim * 2) + c8 * 16));
         const int slot = 16 * (jj >> 4) + key_slot16(jj & 15);
 #pragma unroll
         for (int e = 0; e < 8; ++e) tile[c8 * 8 + e][slot] = (_Float16)(float)x.bf[e];
