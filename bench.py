@@ -742,6 +742,27 @@ def q8_bench(cfg, args, torch, C, W, steps, warmup, want_parity=True):
                         "avg_launch_ms": v_ms},
            "score_kernel_ms": s_ms, "host_wall_ms_per_step": wall_ms}
     if want_parity:
+        # dense multi-head attention over quantised caches: the same kernels with every head its own cluster
+        # (identity maps) over the quantised FULL key cache
+        ident_h2c = torch.arange(H, dtype=torch.int32, device="cuda").repeat(B, 1).contiguous()
+        ws_d = torch.empty((C.chai_decode_q8_workspace_bytes(B, H, H, T),), dtype=torch.uint8, device="cuda")
+        n_dense = len(layers)
+        kq_full = [C.chai_quantize_rows(layers[i].kfull) for i in range(n_dense)]
+
+        def dense_step():
+            for i in range(n_dense):
+                L, (k8, ks, v8, vs) = layers[i], q8[i]
+                C.chai_decode_attention_q8(L.q, kq_full[i][0], kq_full[i][1], v8, vs, ident_h2c, ident_h2c, T, cfg.scale,
+                                           L.out, ws_d)
+
+        d_ms, _ = timed_steps(dense_step, max(steps // 2, 3), warmup, torch)
+        d_ms *= len(layers) / n_dense
+        dense_bytes = len(layers) * (2 * B * H * T * row_bytes)
+        rec["dense_mha_q8"] = {"ms_per_step": d_ms, "tokens_per_s": B / (d_ms * 1e-3),
+                               "GBps": dense_bytes / (d_ms * 1e-3) / 1e9, "speedup_clustered_over_dense": d_ms / ms,
+                               "ideal_speedup_by_bytes": dense_bytes / alg,
+                               "how": "same kernels, identity maps, quantised full key cache, every layer"}
+        del kq_full, ws_d
         from oracle import chai_oracle as O
         step()
         torch.cuda.synchronize()
