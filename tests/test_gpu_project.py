@@ -82,6 +82,52 @@ def test_projection_matches_oracle(B, H, kk, Tn, D, pos0, Tc_cap):
     run_case(B, H, kk, Tn, D, pos0, Tc_cap, seed=B * 5 + H * 3 + Tn, holes=True)
 
 
+@pytest.mark.parametrize("name", ["cfg2", "cfg4"])
+def test_projection_full_size_sampled(name):
+    """The projection at the sizes bench.py --mode project times (all batch rows, positions 5..T-1, the model's
+    width, the benchmark's 0.05-scaled weights).  The oracle computes sampled (batch row, slot, token block) pieces
+    from the bytes downloaded from the device; what holds at any size: every written value is finite, pruned heads'
+    query rows and the cache rows outside the block stay untouched."""
+    cfg = W.CONFIGS[name]
+    B, H, d, T = cfg.B, cfg.H, cfg.d, cfg.T
+    D, kk = H * d, cfg.ks[-1]
+    pos0, Tn = W.N_TOK, T - W.N_TOK
+    print(f"[full-size projection] {name}: B={B} H={H} k={kk} tokens={Tn} width={D}", flush=True)
+    g = W.rng(cfg.seed, 0, "member", extra=11)
+    _, rep = W.random_membership(g, B, H, kk)
+    seed = cfg.seed * 6007
+    x = W.device_normal((B, Tn, D), cfg.dtype, seed + 1)
+    w_q = (W.device_normal((H * d, D), cfg.dtype, seed + 2) * 0.05).to(torch.bfloat16)
+    w_k = (W.device_normal((H * d, D), cfg.dtype, seed + 3) * 0.05).to(torch.bfloat16)
+    q_out = torch.full((B, H, Tn, d), 7.0, dtype=torch.bfloat16, device="cuda")
+    kc = torch.full((B, kk, T, d), 9.0, dtype=torch.bfloat16, device="cuda")
+    C.chai_project_qk(x, w_q, w_k, W.host_to_torch(rep), q_out, kc, pos0)
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(q_out.float()).all()) and bool(torch.isfinite(kc.float()).all())
+    assert bool((kc[:, :, :pos0] == 9.0).all())
+    for b in range(B):
+        pruned = sorted(set(range(H)) - set(int(r) for r in rep[b] if r >= 0))
+        if pruned:
+            assert bool((q_out[b, pruned] == 7.0).all()), "query rows of a pruned head touched"
+    gs = np.random.default_rng(cfg.seed + 17)
+    rows = 8
+    for s in range(8):
+        b, j = int(gs.integers(B)), int(gs.integers(kk))
+        r = int(rep[b, j])
+        if r < 0:
+            continue
+        t0 = [0, 250, Tn - rows, int(gs.integers(Tn - rows))][s % 4]       # first tile, a tile edge, the ragged end
+        xh = W.torch_to_host_bits(x[b:b + 1, t0:t0 + rows])
+        wqh = W.torch_to_host_bits(w_q[r * d:(r + 1) * d])
+        wkh = W.torch_to_host_bits(w_k[r * d:(r + 1) * d])
+        q_ref, k_ref = O.project_qk(xh, wqh, wkh, np.zeros((1, 1), np.int32), d)      # one head: its own weights
+        x64 = np.abs(W.as_f64(xh))[0]
+        check_rounded(W.torch_to_host_bits(q_out[b, r, t0:t0 + rows]), q_ref[0, 0],
+                      np.einsum("te,ce->tc", x64, np.abs(W.as_f64(wqh))), f"{name} q b={b} j={j} rows {t0}..")
+        check_rounded(W.torch_to_host_bits(kc[b, j, pos0 + t0:pos0 + t0 + rows]), k_ref[0, 0],
+                      np.einsum("te,ce->tc", x64, np.abs(W.as_f64(wkh))), f"{name} k b={b} j={j} rows {t0}..")
+
+
 def test_projection_feeds_the_attention_kernels():
     """Projection -> clustered prefill attention, against the oracle fed with the oracle's projections rounded to
     bf16: the layouts the projection writes are the ones the attention kernels read."""
